@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the approximate-gradient-coding hot path on one MI355X.
+
+One step = one agc_step: scale pass -> scale finalize -> encode+quantize+pack -> decode over
+one batch of synthetic partial gradients that is already resident in HBM.  Prints ONE JSON
+line: throughput in GB/s of gradient traffic (4*k*d bytes per step), the roofline view of the
+dominant kernel (HIP-event durations measured in the timed region) and the CPU oracle timed
+on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--scale maxabs|l2]
+                    [--code cyclic|interval] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+VALU_PEAK_GLANEOPS = 256 * 64 * 2.4   # 256 CUs x 64 lanes x 2.4 GHz = 39 321.6 G lane-ops/s
+
+
+def build_problem(cfg, api, code_kind):
+    from paper_2605_15890_amd import inputs as I
+    p = I.straggler_probs(cfg)
+    bits = I.random_bits(cfg)
+    if bits is None:        # bits from the low-complexity allocator at the configured mean budget
+        z_tot = cfg.bits_law[1] * cfg.n
+        bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    if code_kind == "cyclic":
+        row_ptr, col, val, w = api.agc_build_cyclic_code(cfg.n, cfg.k, cfg.s, p, np.maximum(bits, 2), pc)
+    else:
+        row_ptr, col, val, w = api.agc_build_code(cfg.n, cfg.k, p, np.maximum(bits, 2), pc)
+    ok, res = api.agc_check_unbiased(cfg.k, row_ptr, col, val, w, p, 1e-5)
+    assert ok, res
+    return p, bits, (row_ptr, col, val), w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--scale", default="maxabs", choices=["maxabs", "l2"])
+    ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-log2", type=int, default=21)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (the design for "
+              "sharding along d is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_15890_amd import api
+    from paper_2605_15890_amd import inputs as I
+
+    cfg = I.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    scale_mode = api.AGC_SCALE_MAXABS if args.scale == "maxabs" else api.AGC_SCALE_L2
+    p, bits, code, w = build_problem(cfg, api, args.code)
+    n, k, d = cfg.n, cfg.k, cfg.d
+
+    G = I.partial_gradients_torch(cfg, dev)
+    assert G.stride(0) % 4 == 0 and G.data_ptr() % 16 == 0
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit)
+    ctx.agc_set_code(*code)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    K, W = args.steps, args.warmup
+    masks = [I.arrival_mask(cfg, p, t) for t in range(W + K)]     # sampled outside the timed region
+    seed = cfg.philox_seed
+
+    for t in range(W):
+        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
+    torch.cuda.synchronize()
+    ctx.agc_profile_enable(True)
+    ctx.agc_profile_read()
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.agc_profile_read()
+    ctx.agc_profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    grad_bytes = 4.0 * k * d
+    value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # algorithmic bytes per launch of each kernel (what the method must move)
+    sum_b = float(np.sum(bits))
+    arrived_b = float(np.mean([np.sum(bits[m.astype(bool)]) for m in masks[W:]]))
+    alg_bytes = {
+        "scale_pass": 4.0 * k * d,
+        "scale_finalize": 0.0,
+        "quantize": 4.0 * k * d + d * sum_b / 8.0,
+        "decode": d * arrived_b / 8.0 + 4.0 * d,
+    }
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        avg = ms / max(cnt, 1)
+        kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
+                         "alg_GBps": round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1) if avg > 0 else None}
+    dominant = max(kernels, key=lambda nm: kernels[nm]["avg_ms"])
+    dom_avg_s = kernels[dominant]["avg_ms"] * 1e-3
+    achieved = alg_bytes[dominant] / dom_avg_s / 1e9
+    step_alg_bytes = sum(alg_bytes.values())
+    roofline = {
+        "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "avg_launch_ms": kernels[dominant]["avg_ms"],
+        "alg_bytes_per_launch": alg_bytes[dominant],
+        "step_alg_bytes": step_alg_bytes,
+        "step_hbm_frac": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import agc_oracle as O
+        ds = min(d, 1 << args.cpu_sample_log2)
+        Gs = G[:, :ds].contiguous().cpu().numpy()
+        csr = O.Csr(code[0], code[1], code[2], k)
+        c0 = time.perf_counter()
+        O.step(Gs, csr, bits, w, masks[W], seed, W, O.SCALE_MAXABS if args.scale == "maxabs" else O.SCALE_L2)
+        c1 = time.perf_counter()
+        cpu_baseline = {
+            "value": round(4.0 * k * ds / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": O.threads(),
+            "kind": "oracle",
+            "sample": f"one oracle step on the first {ds} of {d} coordinates of all {k} partitions "
+                      f"({n * ds} coded elements), {c1 - c0:.2f} s wall",
+        }
+
+    out = {
+        "metric": "encode+quantize+decode GB/s of gradient traffic",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={n} workers, k={k} partitions, s={cfg.s}, d={d}, "
+                               f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
+                               f"{args.code} code, {args.scale} scale",
+                   "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
+                   "code_path": ctx.agc_code_path()},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,218 @@
+/*
+ * agc.h -- C ABI of the MI355X (gfx950) hot path of communication-efficient approximate
+ * gradient coding: encode -> stochastic quantize + bit-pack -> masked dequantize + decode.
+ *
+ * Symbols (the paper's own letters in brackets): n workers [k], k data partitions [n],
+ * d gradient coordinates [l], code matrix B [A] of shape n x k, partial gradients G
+ * (k x d, row j = g_j), bit-width b_i [z_i], magnitude levels L_i = 2^(b_i-1)-1 [s_i],
+ * decode weights w_i, arrival indicators mask_i [I_i], straggling probabilities p_i.
+ *
+ * General conventions
+ *   - every entry point returns agc_status (0 = ok, negative = error); nothing throws or
+ *     aborts; agc_last_error() gives a message for the last failure on a context;
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory
+ *     of the GPU that was current when the context was created;
+ *   - the caller owns every buffer it passes; the library owns only the workspace it
+ *     allocates in agc_create() and allocates nothing in the per-step calls;
+ *   - per-step calls validate their arguments synchronously, enqueue kernels on the given
+ *     HIP stream (a hipStream_t passed as void*, NULL = the default stream) and return
+ *     without waiting and without any host<->device copy: the small host arrays (bits, w,
+ *     mask, code pointers) travel as kernel arguments;
+ *   - NaN or infinity in G is outside the contract (no check on the hot path).
+ *
+ * Arithmetic fixed by this library (the paper leaves these open; the CPU oracle in
+ * oracle/ takes the same readings):
+ *   encode     binary32; first stored entry of a row: rounded product; each further entry:
+ *              one fused multiply-add, in stored order;
+ *   scale      AGC_SCALE_MAXABS: max_m |f_i[m]|;  AGC_SCALE_L2: (float)sqrt(S) with S the
+ *              binary64 sum of squares in the fixed tree described at agc_encode_quantize;
+ *   draws      Philox4x32-10, key = seed; 16-bit primary field, 32-bit secondary word
+ *              (see agc_encode_quantize);
+ *   payload    per worker a little-endian bit stream, code m in bits [m*b, (m+1)*b),
+ *              zero-padded to whole groups of 128 codes (agc_code_bytes);
+ *   decode     binary32, arrived workers in ascending order, one fused multiply-add each.
+ */
+#ifndef AGC_H
+#define AGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AGC_MAX_WORKERS 256   /* n <= 256: per-worker arguments travel in the kernel argument block */
+#define AGC_MAX_BITS 16
+#define AGC_NUM_KERNELS 4     /* scale pass, scale finalize, encode+quantize+pack, decode */
+
+typedef struct agc_ctx agc_ctx; /* opaque; owns device workspace, a copy of B and timing events */
+
+typedef enum {
+    AGC_OK = 0,
+    AGC_EINVAL = -1, /* null pointer, non-positive size, unknown option value */
+    AGC_ESHAPE = -2, /* n, k, d out of range; CSR malformed; column index out of range */
+    AGC_EBITS = -3,  /* bit-width outside [2,16] (or 1 without allow_1bit) */
+    AGC_EALIGN = -4, /* G or g_hat not 16-byte aligned, ldg not a multiple of 4, stream not 4-byte aligned */
+    AGC_ENOMEM = -5, /* workspace allocation failed */
+    AGC_EHIP = -6,   /* a HIP call failed (message in agc_last_error) */
+    AGC_ESTATE = -7  /* agc_set_code() has not been called */
+} agc_status;
+
+typedef enum {
+    AGC_SCALE_L2 = 0,    /* Euclidean norm: the quantizer of Sec. II-B as printed */
+    AGC_SCALE_MAXABS = 1 /* largest magnitude: finer grid, still unbiased (any scale >= max|f| is) */
+} agc_scale_mode;
+
+typedef struct {
+    int scale_mode;    /* agc_scale_mode */
+    int allow_1bit;    /* non-zero: accept b_i = 1 (two-point grid {-scale,+scale}; outside the paper, which needs b >= 2) */
+    int force_generic; /* non-zero: never take the cyclic-band fast path (testing) */
+    int reserved[5];   /* must be zero */
+} agc_opts;
+
+/* --------------------------------------------------------------------------------------
+ * Context
+ * ------------------------------------------------------------------------------------ */
+/* Creates a context for n workers, k partitions, d coordinates on the current device and
+ * allocates its workspace (per-segment scale partials: about 8*n*ceil(d/4096) bytes).
+ * opts may be NULL (AGC_SCALE_MAXABS, no 1-bit).  Limits: 1 <= n <= AGC_MAX_WORKERS,
+ * 1 <= k <= 65536, 1 <= d <= 2^33. */
+agc_status agc_create(agc_ctx **out, int n_workers, int k_parts, int64_t d, const agc_opts *opts);
+void agc_destroy(agc_ctx *ctx);
+
+/* Sets the code matrix B (Sec. II-A: f_i = sum_j a_ij g_j) as CSR rows over host arrays
+ * row_ptr[n+1], col[nnz], val[nnz]; the arrays are copied (one synchronous upload).  The
+ * order of the stored entries inside a row IS the summation order of the encode.  When
+ * n == k and every row i stores exactly s <= 8 entries with columns (i+u) mod k, u=0..s-1 in
+ * that order (cyclic replication), the kernels take a register sliding-window path that
+ * reads every element of G once per pass; any other B takes the generic gather path.  Both
+ * give identical bits. */
+agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col, const float *val);
+
+/* 0 = generic gather path, s > 0 = cyclic-band path with replication s; < 0 = no code set. */
+int agc_code_path(const agc_ctx *ctx);
+
+/* Bytes of one worker's packed stream: ceil(d/128) * 16 * bits (Sec. II-B: the payload is
+ * the scale plus d codes of b bits; the padding is this library's). */
+int64_t agc_code_bytes(int64_t d, int bits);
+
+const char *agc_last_error(const agc_ctx *ctx);
+
+/* --------------------------------------------------------------------------------------
+ * Hot path
+ * ------------------------------------------------------------------------------------ */
+/*
+ * Worker side (Sec. II-A encoded message, Sec. II-B quantizer): for every worker i
+ *   f_i      = sum_j B[i,j] G[j,:]                      (never written to memory)
+ *   scale_i  per scale_mode over all d coordinates
+ *   code     = sign << (b_i-1) | level,  level = min(floor(T/2^16) + up, L_i),
+ *              T = |f| * inv16_i (binary32), inv16_i = (float)(L_i * 2^16 / scale_i) (0 when
+ *              scale_i is 0 or the quotient overflows), up = U < frac(T/2^16) with the
+ *              48-bit uniform U = (u16 + r2 / 2^32) / 2^16:
+ *                u16 = 16-bit field (i&1)*4 + (m&3) of Philox4x32-10(key = seed,
+ *                      counter = (m>>2, i>>1, step lo, step hi)), fields counted from the
+ *                      low half of output word 0;
+ *                r2  = word m&3 of Philox4x32-10(key = seed, counter = (m>>2, 2^31 | i,
+ *                      step lo, step hi)), consulted only when u16 ties;
+ *              b_i = 1 (allow_1bit): T = max(fma(f, 2^15/scale_i, 2^15), 0), code = level in {0,1};
+ *   stream_i = little-endian bit stream of the d codes.
+ * All n workers are encoded: a straggler still computes, its message is merely late; the
+ * arrival mask is an argument of the decode only.
+ *
+ * AGC_SCALE_L2 tree (binary64): 256-coordinate blocks; slot l of a block owns coordinates
+ * 4l..4l+3 and holds (x0^2+x1^2)+(x2^2+x3^2); exchange-add over slots at distances
+ * 1,2,4,8,16,32; 16 blocks are summed in order into a segment, 64 segments in order into a
+ * group, groups in order into S.
+ *
+ *   G_dev      device, k x d binary32, row-major with row stride ldg elements (ldg >= d,
+ *              ldg % 4 == 0, base 16-byte aligned); read-only
+ *   bits_host  host, n bytes
+ *   codes_dev  host array of n device pointers; stream i has agc_code_bytes(d, b_i) bytes,
+ *              4-byte aligned; fully overwritten, padding included
+ *   scales_dev device, n floats; overwritten
+ */
+agc_status agc_encode_quantize(agc_ctx *ctx, const float *G_dev, int64_t ldg,
+                               const uint8_t *bits_host, uint64_t seed, uint64_t step,
+                               void *const *codes_dev, float *scales_dev, void *hip_stream);
+
+/*
+ * Master side (Sec. II-A aggregation): g_hat[m] = sum over arrived i, ascending, of
+ * coef_i * v_i[m] folded with one binary32 fused multiply-add each from 0, where
+ * coef_i = (float)(((double)w_i * scale_i) / L_i) and v = +-level (b_i >= 2) or +-1 (b_i = 1).
+ *
+ *   codes_dev, scales_dev, bits_host   as written by agc_encode_quantize (read-only)
+ *   w_host     host, n floats: decode weights
+ *   mask_host  host, n bytes: 1 = worker arrived, 0 = straggler (its stream is not read)
+ *   ghat_dev   device, d floats, 16-byte aligned; overwritten
+ */
+agc_status agc_decode(agc_ctx *ctx, void *const *codes_dev, const float *scales_dev,
+                      const uint8_t *bits_host, const float *w_host, const uint8_t *mask_host,
+                      float *ghat_dev, void *hip_stream);
+
+/* One whole pass: agc_encode_quantize followed by agc_decode on the same stream. */
+agc_status agc_step(agc_ctx *ctx, const float *G_dev, int64_t ldg, const uint8_t *bits_host,
+                    const float *w_host, const uint8_t *mask_host, uint64_t seed, uint64_t step,
+                    void *const *codes_dev, float *scales_dev, float *ghat_dev, void *hip_stream);
+
+/* --------------------------------------------------------------------------------------
+ * Per-kernel timing (HIP events recorded on the caller's stream around each kernel)
+ * ------------------------------------------------------------------------------------ */
+/* on != 0: the following hot-path calls bracket each of their kernels with a pair of events
+ * (a ring of 128 pairs per kernel; when the ring is full the oldest pair is drained with one
+ * event synchronisation).  Kernel indices: 0 scale pass, 1 scale finalize,
+ * 2 encode+quantize+pack, 3 decode. */
+agc_status agc_profile_enable(agc_ctx *ctx, int on);
+/* Waits for the recorded events, adds them up and clears the ring: total_ms[j] and
+ * launches[j] for each kernel index j since the previous read. */
+agc_status agc_profile_read(agc_ctx *ctx, double total_ms[AGC_NUM_KERNELS],
+                            int64_t launches[AGC_NUM_KERNELS]);
+
+/* --------------------------------------------------------------------------------------
+ * Host-side design routines (no GPU work; run once per change of the system statistics)
+ * ------------------------------------------------------------------------------------ */
+/* phi(z) = phi_coef / (2^(z-1)-1)^2.  The paper's constant is phi_coef = d/4 (Sec. II-B);
+ * the error-balance scaling of Sec. V-B gives phi_coef = mean(p) * (2^(z_total/n - 1) - 1)^2,
+ * returned by this helper. */
+double agc_phi_coef_balanced(int n, const double *p, int z_total);
+
+/* Low-complexity bit allocation (Sec. III-B.2, Algorithm 1): maximises
+ * F = sum_i (1-p_i)/(p_i + phi(z_i)) subject to sum z_i = z_total, z_min <= z_i <= z_max
+ * (z_max is this library's cap; the paper has none).  Steps the paper leaves open are read
+ * as: Lagrangian candidate by bisection on the multiplier with each active worker on the
+ * concave branch of its utility, rounded by largest remainder; equal candidate
+ * floor/ceil; best-improvement one-bit swaps inside the active set.  bits_out: n bytes. */
+agc_status agc_alloc_bits(int n, const double *p, double phi_coef, int z_total, int z_min,
+                          int z_max, uint8_t *bits_out);
+/* Optimal allocation by the Bellman recurrence of Sec. III-B.1 (O(n * z_res^2)). */
+agc_status agc_alloc_bits_dp(int n, const double *p, double phi_coef, int z_total, int z_min,
+                             int z_max, uint8_t *bits_out);
+/* F(z) of problem b-SP1 for a given allocation. */
+double agc_alloc_objective(int n, const double *p, double phi_coef, const uint8_t *bits);
+
+/* Optimally structured sparse code (Theorem 1 and the interval construction of Sec. III-A):
+ * c_i = (p_i + phi(b_i))/(1-p_i), Y_i = c_i^-1 k / sum c^-1, R_i = prefix sums,
+ * alpha_ij = [min(R_i, j) - max(R_{i-1}, j-1)]_+, then a_ij = alpha_ij, w_i = 1/(1-p_i)
+ * (the free factor w~_i is taken as 1).  Outputs: CSR over caller arrays row_ptr[n+1],
+ * col[cap], val[cap] with columns ascending, w_out[n]; *nnz receives the count
+ * (<= n + k - 1); cap is the capacity of col/val (AGC_ESHAPE when too small). */
+agc_status agc_build_code(int n, int k, const double *p, const uint8_t *bits, double phi_coef,
+                          int32_t *row_ptr, int32_t *col, float *val, float *w_out, int cap,
+                          int *nnz);
+/* Code on the cyclic support {i, .., i+s-1 mod k} (n == k): alpha_ij = c_i^-1 / (sum of
+ * c^-1 over the workers holding j); column sums are 1, so the estimator is unbiased; it is a
+ * heuristic on a prescribed support, not Theorem 1's optimum.  col/val hold n*s entries in
+ * the order u = 0..s-1. */
+agc_status agc_build_cyclic_code(int n, int k, int s, const double *p, const uint8_t *bits,
+                                 double phi_coef, int32_t *row_ptr, int32_t *col, float *val,
+                                 float *w_out);
+/* Unbiasedness condition of Sec. III: max_j | sum_i (1-p_i) w_i a_ij - 1 | <= tol (binary64
+ * over the binary32 inputs).  AGC_OK when it holds, AGC_EINVAL when it does not;
+ * *residual (may be NULL) receives the maximum. */
+agc_status agc_check_unbiased(int n, int k, const int32_t *row_ptr, const int32_t *col,
+                              const float *val, const float *w, const double *p, double tol,
+                              double *residual);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGC_H */

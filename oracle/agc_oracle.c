@@ -153,9 +153,10 @@ float agc_oracle_scale_maxabs(const float *f, int64_t d)
  *            slot value = (x0^2 + x1^2) + (x2^2 + x3^2);
  *   level 1  exchange-add over slots with distances 1,2,4,8,16,32
  *            (v[l] <- v[l] + v[l xor h]); block value = v[0];
- *   level 2  16 consecutive blocks form a segment: sequential sum from 0.0;
+ *   level 2  4 consecutive blocks form a segment: sequential sum from 0.0;
  *   level 3  64 consecutive segments form a group: sequential sum from 0.0;
- *   level 4  groups: sequential sum from 0.0.
+ *   level 4  64 consecutive groups form a supergroup: sequential sum from 0.0;
+ *   level 5  supergroups: sequential sum from 0.0.
  * scale = (float) sqrt(total).
  */
 static double l2_block(const float *f, int64_t d, int64_t block)
@@ -181,18 +182,23 @@ static double l2_block(const float *f, int64_t d, int64_t block)
 double agc_oracle_sumsq_tree(const float *f, int64_t d)
 {
     int64_t nblocks = (d + 255) / 256;
-    int64_t nsegs = (nblocks + 15) / 16;
+    int64_t nsegs = (nblocks + 3) / 4;
     int64_t ngroups = (nsegs + 63) / 64;
+    int64_t nsuper = (ngroups + 63) / 64;
     double total = 0.0;
-    for (int64_t g = 0; g < ngroups; ++g) {
-        double gsum = 0.0;
-        for (int64_t s = g * 64; s < (g + 1) * 64 && s < nsegs; ++s) {
-            double ssum = 0.0;
-            for (int64_t b = s * 16; b < (s + 1) * 16 && b < nblocks; ++b)
-                ssum = ssum + l2_block(f, d, b);
-            gsum = gsum + ssum;
+    for (int64_t u = 0; u < nsuper; ++u) {
+        double usum = 0.0;
+        for (int64_t g = u * 64; g < (u + 1) * 64 && g < ngroups; ++g) {
+            double gsum = 0.0;
+            for (int64_t s = g * 64; s < (g + 1) * 64 && s < nsegs; ++s) {
+                double ssum = 0.0;
+                for (int64_t b = s * 4; b < (s + 1) * 4 && b < nblocks; ++b)
+                    ssum = ssum + l2_block(f, d, b);
+                gsum = gsum + ssum;
+            }
+            usum = usum + gsum;
         }
-        total = total + gsum;
+        total = total + usum;
     }
     return total;
 }

@@ -1,0 +1,285 @@
+"""Thin ctypes binding of include/agc.h: same names, argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libagc.so; torch is used for device
+memory and for the current stream.  `load()` raises if the library has not been built: there
+is no fallback of any kind.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libagc.so")
+
+AGC_OK = 0
+AGC_EINVAL, AGC_ESHAPE, AGC_EBITS, AGC_EALIGN, AGC_ENOMEM, AGC_EHIP, AGC_ESTATE = -1, -2, -3, -4, -5, -6, -7
+AGC_SCALE_L2, AGC_SCALE_MAXABS = 0, 1
+AGC_MAX_WORKERS, AGC_MAX_BITS, AGC_NUM_KERNELS = 256, 16, 4
+KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
+
+EXPORTS = [
+    "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
+    "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
+    "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
+    "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
+]
+
+
+class AgcOpts(C.Structure):
+    _fields_ = [("scale_mode", C.c_int), ("allow_1bit", C.c_int), ("force_generic", C.c_int),
+                ("reserved", C.c_int * 5)]
+
+
+class AgcError(RuntimeError):
+    def __init__(self, status, message=""):
+        super().__init__(f"agc status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+_vp, _u8p, _i32p, _f32p, _f64p = (C.c_void_p, C.POINTER(C.c_uint8), C.POINTER(C.c_int32),
+                                  C.POINTER(C.c_float), C.POINTER(C.c_double))
+
+
+def load():
+    """Loads libagc.so (built by `python -m paper_2605_15890_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_15890_amd.build`; "
+                           "there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    L.agc_create.argtypes = [C.POINTER(_vp), C.c_int, C.c_int, C.c_int64, C.POINTER(AgcOpts)]
+    L.agc_create.restype = C.c_int
+    L.agc_destroy.argtypes = [_vp]
+    L.agc_destroy.restype = None
+    L.agc_set_code.argtypes = [_vp, _i32p, _i32p, _f32p]
+    L.agc_set_code.restype = C.c_int
+    L.agc_code_path.argtypes = [_vp]
+    L.agc_code_path.restype = C.c_int
+    L.agc_code_bytes.argtypes = [C.c_int64, C.c_int]
+    L.agc_code_bytes.restype = C.c_int64
+    L.agc_last_error.argtypes = [_vp]
+    L.agc_last_error.restype = C.c_char_p
+    L.agc_encode_quantize.argtypes = [_vp, _vp, C.c_int64, _u8p, C.c_uint64, C.c_uint64,
+                                      C.POINTER(_vp), _vp, _vp]
+    L.agc_encode_quantize.restype = C.c_int
+    L.agc_decode.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _u8p, _vp, _vp]
+    L.agc_decode.restype = C.c_int
+    L.agc_step.argtypes = [_vp, _vp, C.c_int64, _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64,
+                           C.POINTER(_vp), _vp, _vp, _vp]
+    L.agc_step.restype = C.c_int
+    L.agc_profile_enable.argtypes = [_vp, C.c_int]
+    L.agc_profile_enable.restype = C.c_int
+    L.agc_profile_read.argtypes = [_vp, _f64p, C.POINTER(C.c_int64)]
+    L.agc_profile_read.restype = C.c_int
+    L.agc_phi_coef_balanced.argtypes = [C.c_int, _f64p, C.c_int]
+    L.agc_phi_coef_balanced.restype = C.c_double
+    for name in ("agc_alloc_bits", "agc_alloc_bits_dp"):
+        fn = getattr(L, name)
+        fn.argtypes = [C.c_int, _f64p, C.c_double, C.c_int, C.c_int, C.c_int, _u8p]
+        fn.restype = C.c_int
+    L.agc_alloc_objective.argtypes = [C.c_int, _f64p, C.c_double, _u8p]
+    L.agc_alloc_objective.restype = C.c_double
+    L.agc_build_code.argtypes = [C.c_int, C.c_int, _f64p, _u8p, C.c_double, _i32p, _i32p, _f32p,
+                                 _f32p, C.c_int, C.POINTER(C.c_int)]
+    L.agc_build_code.restype = C.c_int
+    L.agc_build_cyclic_code.argtypes = [C.c_int, C.c_int, C.c_int, _f64p, _u8p, C.c_double, _i32p,
+                                        _i32p, _f32p, _f32p]
+    L.agc_build_cyclic_code.restype = C.c_int
+    L.agc_check_unbiased.argtypes = [C.c_int, C.c_int, _i32p, _i32p, _f32p, _f32p, _f64p,
+                                     C.c_double, _f64p]
+    L.agc_check_unbiased.restype = C.c_int
+    _lib = L
+    return L
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a, ptype):
+    return a.ctypes.data_as(ptype)
+
+
+# --------------------------------------------------------------------------- host routines
+def agc_code_bytes(d, bits):
+    return int(load().agc_code_bytes(int(d), int(bits)))
+
+
+def agc_phi_coef_balanced(p, z_total):
+    p = _np(p, np.float64)
+    return float(load().agc_phi_coef_balanced(len(p), _ptr(p, _f64p), int(z_total)))
+
+
+def _alloc(fn, p, phi_coef, z_total, z_min, z_max):
+    p = _np(p, np.float64)
+    out = np.zeros(len(p), dtype=np.uint8)
+    st = fn(len(p), _ptr(p, _f64p), float(phi_coef), int(z_total), int(z_min), int(z_max), _ptr(out, _u8p))
+    if st != AGC_OK:
+        raise AgcError(st, "bit allocation")
+    return out
+
+
+def agc_alloc_bits(p, phi_coef, z_total, z_min=2, z_max=8):
+    return _alloc(load().agc_alloc_bits, p, phi_coef, z_total, z_min, z_max)
+
+
+def agc_alloc_bits_dp(p, phi_coef, z_total, z_min=2, z_max=8):
+    return _alloc(load().agc_alloc_bits_dp, p, phi_coef, z_total, z_min, z_max)
+
+
+def agc_alloc_objective(p, phi_coef, bits):
+    p = _np(p, np.float64)
+    bits = _np(bits, np.uint8)
+    return float(load().agc_alloc_objective(len(p), _ptr(p, _f64p), float(phi_coef), _ptr(bits, _u8p)))
+
+
+def agc_build_code(n, k, p, bits, phi_coef):
+    """Returns (row_ptr, col, val, w) of the optimally structured interval code."""
+    p = _np(p, np.float64)
+    bits = _np(bits, np.uint8)
+    cap = n + k
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col = np.zeros(cap, dtype=np.int32)
+    val = np.zeros(cap, dtype=np.float32)
+    w = np.zeros(n, dtype=np.float32)
+    nnz = C.c_int()
+    st = load().agc_build_code(n, k, _ptr(p, _f64p), _ptr(bits, _u8p), float(phi_coef), _ptr(row_ptr, _i32p),
+                               _ptr(col, _i32p), _ptr(val, _f32p), _ptr(w, _f32p), cap, C.byref(nnz))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_build_code")
+    return row_ptr, col[:nnz.value].copy(), val[:nnz.value].copy(), w
+
+
+def agc_build_cyclic_code(n, k, s, p, bits, phi_coef):
+    p = _np(p, np.float64)
+    bits = _np(bits, np.uint8)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col = np.zeros(n * s, dtype=np.int32)
+    val = np.zeros(n * s, dtype=np.float32)
+    w = np.zeros(n, dtype=np.float32)
+    st = load().agc_build_cyclic_code(n, k, s, _ptr(p, _f64p), _ptr(bits, _u8p), float(phi_coef),
+                                      _ptr(row_ptr, _i32p), _ptr(col, _i32p), _ptr(val, _f32p), _ptr(w, _f32p))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_build_cyclic_code")
+    return row_ptr, col, val, w
+
+
+def agc_check_unbiased(k, row_ptr, col, val, w, p, tol=1e-5):
+    """Returns (holds: bool, residual)."""
+    row_ptr, col, val = _np(row_ptr, np.int32), _np(col, np.int32), _np(val, np.float32)
+    w, p = _np(w, np.float32), _np(p, np.float64)
+    res = C.c_double()
+    st = load().agc_check_unbiased(len(row_ptr) - 1, int(k), _ptr(row_ptr, _i32p), _ptr(col, _i32p),
+                                   _ptr(val, _f32p), _ptr(w, _f32p), _ptr(p, _f64p), float(tol), C.byref(res))
+    if st not in (AGC_OK, AGC_EINVAL):
+        raise AgcError(st, "agc_check_unbiased")
+    return st == AGC_OK, float(res.value)
+
+
+# --------------------------------------------------------------------------- hot path
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+class Context:
+    """Owns an agc_ctx and, for convenience, torch buffers for codes / scales / g_hat."""
+
+    def __init__(self, n, k, d, scale_mode=AGC_SCALE_MAXABS, allow_1bit=False, force_generic=False):
+        self.lib = load()
+        self.n, self.k, self.d = int(n), int(k), int(d)
+        opts = AgcOpts(int(scale_mode), int(bool(allow_1bit)), int(bool(force_generic)), (C.c_int * 5)())
+        h = _vp()
+        st = self.lib.agc_create(C.byref(h), self.n, self.k, self.d, C.byref(opts))
+        if st != AGC_OK:
+            raise AgcError(st, "agc_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.agc_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        self.close()
+
+    def _check(self, st):
+        if st != AGC_OK:
+            raise AgcError(st, self.lib.agc_last_error(self.h).decode())
+
+    def status_of(self, st):
+        return st
+
+    def agc_set_code(self, row_ptr, col, val):
+        row_ptr, col, val = _np(row_ptr, np.int32), _np(col, np.int32), _np(val, np.float32)
+        self._check(self.lib.agc_set_code(self.h, _ptr(row_ptr, _i32p), _ptr(col, _i32p), _ptr(val, _f32p)))
+
+    def agc_code_path(self):
+        return int(self.lib.agc_code_path(self.h))
+
+    # ---- buffers (torch: device memory only)
+    def alloc_outputs(self, bits, device="cuda"):
+        import torch
+        bits = _np(bits, np.uint8)
+        codes = [torch.empty(agc_code_bytes(self.d, int(b)), dtype=torch.uint8, device=device) for b in bits]
+        scales = torch.empty(self.n, dtype=torch.float32, device=device)
+        ghat = torch.empty(self.d, dtype=torch.float32, device=device)
+        return codes, scales, ghat
+
+    @staticmethod
+    def _code_ptrs(codes):
+        arr = (_vp * len(codes))()
+        for i, t in enumerate(codes):
+            arr[i] = t.data_ptr()
+        return arr
+
+    def agc_encode_quantize(self, G, bits, seed, step, codes, scales, stream=None, check=True):
+        bits = _np(bits, np.uint8)
+        st = self.lib.agc_encode_quantize(self.h, C.c_void_p(G.data_ptr()), G.stride(0), _ptr(bits, _u8p),
+                                          int(seed), int(step), self._code_ptrs(codes),
+                                          C.c_void_p(scales.data_ptr()), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def agc_decode(self, codes, scales, bits, w, mask, ghat, stream=None, check=True):
+        bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
+        st = self.lib.agc_decode(self.h, self._code_ptrs(codes), C.c_void_p(scales.data_ptr()),
+                                 _ptr(bits, _u8p), _ptr(w, _f32p), _ptr(mask, _u8p),
+                                 C.c_void_p(ghat.data_ptr()), _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def agc_step(self, G, bits, w, mask, seed, step, codes, scales, ghat, stream=None, check=True):
+        bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
+        st = self.lib.agc_step(self.h, C.c_void_p(G.data_ptr()), G.stride(0), _ptr(bits, _u8p), _ptr(w, _f32p),
+                               _ptr(mask, _u8p), int(seed), int(step), self._code_ptrs(codes),
+                               C.c_void_p(scales.data_ptr()), C.c_void_p(ghat.data_ptr()),
+                               _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
+    def agc_profile_enable(self, on=True):
+        self._check(self.lib.agc_profile_enable(self.h, int(bool(on))))
+
+    def agc_profile_read(self):
+        ms = (C.c_double * AGC_NUM_KERNELS)()
+        cnt = (C.c_int64 * AGC_NUM_KERNELS)()
+        self._check(self.lib.agc_profile_read(self.h, ms, cnt))
+        return {KERNEL_NAMES[j]: (float(ms[j]), int(cnt[j])) for j in range(AGC_NUM_KERNELS)}
+
+
+def padded_rows(k, d, device="cuda"):
+    """A k x d float32 view whose row stride is a multiple of 4 elements and whose base is
+    16-byte aligned, as agc_encode_quantize requires."""
+    import torch
+    ld = (d + 3) // 4 * 4
+    return torch.zeros((k, ld), dtype=torch.float32, device=device)[:, :d]

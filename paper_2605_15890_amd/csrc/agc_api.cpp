@@ -1,0 +1,389 @@
+// C ABI of the hot path (include/agc.h): context management, synchronous argument
+// validation, kernel launches on the caller's stream, optional per-kernel event timing.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/agc.h"
+#include "agc_kernels.h"
+
+namespace {
+
+constexpr int kEventRing = 128;
+
+struct EventPair {
+    hipEvent_t beg = nullptr, end = nullptr;
+};
+
+}  // namespace
+
+struct agc_ctx {
+    int n = 0, k = 0;
+    int64_t d = 0;
+    agc_opts opts{};
+    int device = 0;
+    // code matrix
+    bool has_code = false;
+    int nnz = 0;
+    int* d_row_ptr = nullptr;
+    int* d_col = nullptr;
+    float* d_val = nullptr;
+    int band = 0;
+    // workspace
+    agc::Workspace ws{};
+    // profiling
+    bool profiling = false;
+    std::vector<EventPair> events[AGC_NUM_KERNELS];
+    int ev_head[AGC_NUM_KERNELS] = {0, 0, 0, 0};   // next slot to record
+    int ev_count[AGC_NUM_KERNELS] = {0, 0, 0, 0};  // recorded, not yet drained
+    double ev_ms[AGC_NUM_KERNELS] = {0, 0, 0, 0};
+    int64_t ev_launches[AGC_NUM_KERNELS] = {0, 0, 0, 0};
+    std::string err;
+};
+
+namespace {
+
+agc_status fail(agc_ctx* ctx, agc_status st, const std::string& msg)
+{
+    if (ctx) ctx->err = msg;
+    return st;
+}
+
+agc_status hip_fail(agc_ctx* ctx, hipError_t e, const char* what)
+{
+    return fail(ctx, AGC_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+template <class T>
+hipError_t dev_alloc(T** p, size_t count)
+{
+    return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
+}
+
+void free_code(agc_ctx* c)
+{
+    if (c->d_row_ptr) (void)hipFree(c->d_row_ptr);
+    if (c->d_col) (void)hipFree(c->d_col);
+    if (c->d_val) (void)hipFree(c->d_val);
+    c->d_row_ptr = nullptr;
+    c->d_col = nullptr;
+    c->d_val = nullptr;
+    c->has_code = false;
+}
+
+// drains the oldest recorded pair of kernel j into the totals
+agc_status drain_one(agc_ctx* c, int j)
+{
+    const int slot = (c->ev_head[j] - c->ev_count[j] + kEventRing) % kEventRing;
+    EventPair& ep = c->events[j][slot];
+    hipError_t e = hipEventSynchronize(ep.end);
+    if (e != hipSuccess) return hip_fail(c, e, "hipEventSynchronize");
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, ep.beg, ep.end);
+    if (e != hipSuccess) return hip_fail(c, e, "hipEventElapsedTime");
+    c->ev_ms[j] += ms;
+    c->ev_launches[j] += 1;
+    c->ev_count[j] -= 1;
+    return AGC_OK;
+}
+
+struct KernelTimer {
+    agc_ctx* c;
+    int j;
+    hipStream_t stream;
+    EventPair* ep = nullptr;
+    agc_status begin()
+    {
+        if (!c->profiling) return AGC_OK;
+        if (c->ev_count[j] == kEventRing) {
+            agc_status st = drain_one(c, j);
+            if (st != AGC_OK) return st;
+        }
+        ep = &c->events[j][c->ev_head[j]];
+        hipError_t e = hipEventRecord(ep->beg, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "hipEventRecord");
+        return AGC_OK;
+    }
+    agc_status end()
+    {
+        if (!c->profiling) return AGC_OK;
+        hipError_t e = hipEventRecord(ep->end, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "hipEventRecord");
+        c->ev_head[j] = (c->ev_head[j] + 1) % kEventRing;
+        c->ev_count[j] += 1;
+        return AGC_OK;
+    }
+};
+
+agc_status check_bits(agc_ctx* c, const uint8_t* bits)
+{
+    for (int i = 0; i < c->n; ++i) {
+        const int b = bits[i];
+        if (b > AGC_MAX_BITS || b < 1 || (b == 1 && !c->opts.allow_1bit))
+            return fail(c, AGC_EBITS, "bit-width of worker " + std::to_string(i) + " is " +
+                                          std::to_string(b) + " (allowed: " +
+                                          (c->opts.allow_1bit ? "1" : "2") + "..16)");
+    }
+    return AGC_OK;
+}
+
+agc_status check_streams(agc_ctx* c, void* const* codes)
+{
+    for (int i = 0; i < c->n; ++i) {
+        if (!codes[i]) return fail(c, AGC_EINVAL, "codes_dev[" + std::to_string(i) + "] is null");
+        if (reinterpret_cast<uintptr_t>(codes[i]) & 3u)
+            return fail(c, AGC_EALIGN, "codes_dev[" + std::to_string(i) + "] is not 4-byte aligned");
+    }
+    return AGC_OK;
+}
+
+agc::CodeDev code_dev(const agc_ctx* c)
+{
+    return agc::CodeDev{c->d_row_ptr, c->d_col, c->d_val, c->opts.force_generic ? 0 : c->band};
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t agc_code_bytes(int64_t d, int bits)
+{
+    if (d <= 0 || bits < 1 || bits > AGC_MAX_BITS) return 0;
+    return ((d + 127) / 128) * 16 * (int64_t)bits;
+}
+
+const char* agc_last_error(const agc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* opts)
+{
+    if (!out) return AGC_EINVAL;
+    *out = nullptr;
+    if (n < 1 || n > AGC_MAX_WORKERS || k < 1 || k > 65536 || d < 1 || d > ((int64_t)1 << 33))
+        return AGC_ESHAPE;
+    agc_opts o{};
+    o.scale_mode = AGC_SCALE_MAXABS;
+    if (opts) {
+        o = *opts;
+        if (o.scale_mode != AGC_SCALE_L2 && o.scale_mode != AGC_SCALE_MAXABS) return AGC_EINVAL;
+        for (int r : o.reserved)
+            if (r != 0) return AGC_EINVAL;
+    }
+    agc_ctx* c = new (std::nothrow) agc_ctx;
+    if (!c) return AGC_ENOMEM;
+    c->n = n;
+    c->k = k;
+    c->d = d;
+    c->opts = o;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return AGC_EHIP;
+    }
+    const int64_t nblocks = (d + 255) / 256;
+    c->ws.nseg = (nblocks + 3) / 4;
+    c->ws.ngroup = (c->ws.nseg + 63) / 64;
+    c->ws.nsuper = (c->ws.ngroup + 63) / 64;
+    hipError_t e = hipSuccess;
+    if (o.scale_mode == AGC_SCALE_MAXABS) {
+        e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nseg * n);
+    } else {
+        e = dev_alloc(&c->ws.part_sq, (size_t)c->ws.nseg * n);
+        if (e == hipSuccess) e = dev_alloc(&c->ws.group_sq, (size_t)c->ws.ngroup * n);
+        if (e == hipSuccess) e = dev_alloc(&c->ws.super_sq, (size_t)c->ws.nsuper * n);
+    }
+    if (e == hipSuccess) e = dev_alloc(&c->ws.inv16, (size_t)n);
+    if (e != hipSuccess) {
+        agc_destroy(c);
+        return e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP;
+    }
+    *out = c;
+    return AGC_OK;
+}
+
+void agc_destroy(agc_ctx* c)
+{
+    if (!c) return;
+    free_code(c);
+    if (c->ws.part_max) (void)hipFree(c->ws.part_max);
+    if (c->ws.part_sq) (void)hipFree(c->ws.part_sq);
+    if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
+    if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
+    if (c->ws.inv16) (void)hipFree(c->ws.inv16);
+    for (auto& ring : c->events)
+        for (auto& ep : ring) {
+            if (ep.beg) (void)hipEventDestroy(ep.beg);
+            if (ep.end) (void)hipEventDestroy(ep.end);
+        }
+    delete c;
+}
+
+agc_status agc_set_code(agc_ctx* c, const int32_t* row_ptr, const int32_t* col, const float* val)
+{
+    if (!c) return AGC_EINVAL;
+    if (!row_ptr) return fail(c, AGC_EINVAL, "row_ptr is null");
+    if (row_ptr[0] != 0) return fail(c, AGC_ESHAPE, "row_ptr[0] must be 0");
+    for (int i = 0; i < c->n; ++i)
+        if (row_ptr[i + 1] < row_ptr[i]) return fail(c, AGC_ESHAPE, "row_ptr must be non-decreasing");
+    const int nnz = row_ptr[c->n];
+    if (nnz > 0 && (!col || !val)) return fail(c, AGC_EINVAL, "col/val are null");
+    for (int e = 0; e < nnz; ++e)
+        if (col[e] < 0 || col[e] >= c->k)
+            return fail(c, AGC_ESHAPE, "column index " + std::to_string(col[e]) + " out of range");
+    // cyclic band: n == k and row i stores exactly s entries (i+u) mod k, u = 0..s-1, in order
+    int band = 0;
+    if (c->n == c->k && nnz > 0 && nnz % c->n == 0) {
+        const int s = nnz / c->n;
+        bool ok = s >= 1 && s <= 8 && s <= c->k;
+        for (int i = 0; ok && i < c->n; ++i) {
+            ok = row_ptr[i] == i * s;
+            for (int u = 0; ok && u < s; ++u) ok = col[i * s + u] == (i + u) % c->k;
+        }
+        if (ok) band = s;
+    }
+    free_code(c);
+    hipError_t e = dev_alloc(&c->d_row_ptr, (size_t)c->n + 1);
+    if (e == hipSuccess) e = dev_alloc(&c->d_col, (size_t)(nnz > 0 ? nnz : 1));
+    if (e == hipSuccess) e = dev_alloc(&c->d_val, (size_t)(nnz > 0 ? nnz : 1));
+    if (e == hipSuccess) e = hipMemcpy(c->d_row_ptr, row_ptr, sizeof(int) * ((size_t)c->n + 1), hipMemcpyHostToDevice);
+    if (e == hipSuccess && nnz > 0) e = hipMemcpy(c->d_col, col, sizeof(int) * (size_t)nnz, hipMemcpyHostToDevice);
+    if (e == hipSuccess && nnz > 0) e = hipMemcpy(c->d_val, val, sizeof(float) * (size_t)nnz, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        free_code(c);
+        return hip_fail(c, e, "uploading the code matrix");
+    }
+    c->nnz = nnz;
+    c->band = band;
+    c->has_code = true;
+    return AGC_OK;
+}
+
+int agc_code_path(const agc_ctx* c)
+{
+    if (!c || !c->has_code) return -1;
+    return c->opts.force_generic ? 0 : c->band;
+}
+
+agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits,
+                               uint64_t seed, uint64_t step, void* const* codes, float* scales,
+                               void* hip_stream)
+{
+    if (!c) return AGC_EINVAL;
+    if (!c->has_code) return fail(c, AGC_ESTATE, "agc_set_code() has not been called");
+    if (!G || !bits || !codes || !scales) return fail(c, AGC_EINVAL, "null argument");
+    if (ldg < c->d || (ldg & 3)) return fail(c, AGC_EALIGN, "ldg must be >= d and a multiple of 4");
+    if (reinterpret_cast<uintptr_t>(G) & 15u) return fail(c, AGC_EALIGN, "G_dev is not 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(scales) & 3u) return fail(c, AGC_EALIGN, "scales_dev is not 4-byte aligned");
+    agc_status st = check_bits(c, bits);
+    if (st != AGC_OK) return st;
+    st = check_streams(c, codes);
+    if (st != AGC_OK) return st;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    const agc::CodeDev code = code_dev(c);
+    agc::PerWorkerBits pb{};
+    agc::QuantStreams qs{};
+    for (int i = 0; i < c->n; ++i) {
+        pb.bits[i] = bits[i];
+        qs.bits[i] = bits[i];
+        qs.codes[i] = codes[i];
+    }
+    hipError_t e;
+    {
+        KernelTimer t{c, 0, stream};
+        if ((st = t.begin()) != AGC_OK) return st;
+        e = agc::launch_scale_pass(G, ldg, c->n, c->k, c->d, code, c->opts.scale_mode, c->ws, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "scale pass launch");
+        if ((st = t.end()) != AGC_OK) return st;
+    }
+    {
+        KernelTimer t{c, 1, stream};
+        if ((st = t.begin()) != AGC_OK) return st;
+        e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, pb, c->ws, scales, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "scale finalize launch");
+        if ((st = t.end()) != AGC_OK) return st;
+    }
+    {
+        KernelTimer t{c, 2, stream};
+        if ((st = t.begin()) != AGC_OK) return st;
+        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, qs, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "quantize launch");
+        if ((st = t.end()) != AGC_OK) return st;
+    }
+    return AGC_OK;
+}
+
+agc_status agc_decode(agc_ctx* c, void* const* codes, const float* scales, const uint8_t* bits,
+                      const float* w, const uint8_t* mask, float* ghat, void* hip_stream)
+{
+    if (!c) return AGC_EINVAL;
+    if (!codes || !scales || !bits || !w || !mask || !ghat) return fail(c, AGC_EINVAL, "null argument");
+    if (reinterpret_cast<uintptr_t>(ghat) & 15u) return fail(c, AGC_EALIGN, "ghat_dev is not 16-byte aligned");
+    agc_status st = check_bits(c, bits);
+    if (st != AGC_OK) return st;
+    st = check_streams(c, codes);
+    if (st != AGC_OK) return st;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    agc::DecodeStreams ds{};
+    for (int i = 0; i < c->n; ++i) {
+        ds.codes[i] = codes[i];
+        ds.w[i] = w[i];
+        ds.bits[i] = bits[i];
+        ds.mask[i] = mask[i] ? 1 : 0;
+    }
+    KernelTimer t{c, 3, stream};
+    if ((st = t.begin()) != AGC_OK) return st;
+    hipError_t e = agc::launch_decode(c->n, c->d, ds, scales, ghat, stream);
+    if (e != hipSuccess) return hip_fail(c, e, "decode launch");
+    return t.end();
+}
+
+agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits, const float* w,
+                    const uint8_t* mask, uint64_t seed, uint64_t step, void* const* codes,
+                    float* scales, float* ghat, void* hip_stream)
+{
+    if (!c) return AGC_EINVAL;
+    // validate the decode arguments before anything is enqueued
+    if (!w || !mask || !ghat) return fail(c, AGC_EINVAL, "null argument");
+    if (reinterpret_cast<uintptr_t>(ghat) & 15u) return fail(c, AGC_EALIGN, "ghat_dev is not 16-byte aligned");
+    agc_status st = agc_encode_quantize(c, G, ldg, bits, seed, step, codes, scales, hip_stream);
+    if (st != AGC_OK) return st;
+    return agc_decode(c, codes, scales, bits, w, mask, ghat, hip_stream);
+}
+
+agc_status agc_profile_enable(agc_ctx* c, int on)
+{
+    if (!c) return AGC_EINVAL;
+    if (on && c->events[0].empty()) {
+        for (auto& ring : c->events) {
+            ring.resize(kEventRing);
+            for (auto& ep : ring) {
+                hipError_t e = hipEventCreate(&ep.beg);
+                if (e == hipSuccess) e = hipEventCreate(&ep.end);
+                if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+            }
+        }
+    }
+    c->profiling = on != 0;
+    return AGC_OK;
+}
+
+agc_status agc_profile_read(agc_ctx* c, double total_ms[AGC_NUM_KERNELS],
+                            int64_t launches[AGC_NUM_KERNELS])
+{
+    if (!c || !total_ms || !launches) return AGC_EINVAL;
+    for (int j = 0; j < AGC_NUM_KERNELS; ++j) {
+        while (c->ev_count[j] > 0) {
+            agc_status st = drain_one(c, j);
+            if (st != AGC_OK) return st;
+        }
+        total_ms[j] = c->ev_ms[j];
+        launches[j] = c->ev_launches[j];
+        c->ev_ms[j] = 0.0;
+        c->ev_launches[j] = 0;
+    }
+    return AGC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,258 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Codes must be bit-exact (flip count 0), scales equal, decode within 1e-5 relative L2
+(checked, and in fact identical because both sides follow one operation-by-operation
+definition)."""
+import numpy as np
+import pytest
+
+from oracle import agc_oracle as O
+from paper_2605_15890_amd import api
+from paper_2605_15890_amd import inputs as I
+
+from gpu_util import compare_with_oracle, cyclic_csr, random_csr, run_hip, to_device
+
+pytestmark = pytest.mark.gpu
+
+MODES = [api.AGC_SCALE_MAXABS, api.AGC_SCALE_L2]
+
+
+def _config_code(cfg, p, bits):
+    """Cyclic code of the configuration from the library's host routine."""
+    pc = api.agc_phi_coef_balanced(p, int(np.sum(bits)))
+    return api.agc_build_cyclic_code(cfg.n, cfg.k, cfg.s, p, np.maximum(bits, 2), pc)
+
+
+@pytest.mark.parametrize("scale_mode", MODES)
+@pytest.mark.parametrize("force_generic", [False, True])
+def test_tiny_config_full_parity(scale_mode, force_generic):
+    cfg = I.CONFIGS["tiny"]
+    p, bits = I.straggler_probs(cfg), I.random_bits(cfg)
+    row_ptr, col, val, w = _config_code(cfg, p, bits)
+    G = I.partial_gradients_numpy(cfg)
+    Gd = to_device(G)
+    for it in range(3):
+        mask = I.arrival_mask(cfg, p, it)
+        out = run_hip(Gd, cfg.n, cfg.k, cfg.d, row_ptr, col, val, bits, w, mask, cfg.philox_seed, it,
+                      scale_mode, force_generic=force_generic, expect_path=0 if force_generic else cfg.s)
+        compare_with_oracle(G, cfg.k, row_ptr, col, val, bits, w, mask, cfg.philox_seed, it, scale_mode,
+                            out, tag=f"tiny it={it}")
+
+
+@pytest.mark.parametrize("d", [1, 3, 4, 5, 127, 128, 129, 255, 256, 257, 1000, 1023, 1025, 4097, 70001])
+def test_ragged_sizes_cyclic_and_generic(d):
+    """Sizes around every tile boundary (float4, 128-code group, 256-coordinate block, 1024
+    segment/workgroup), mixed bit-widths including 1 and 16."""
+    rng = np.random.default_rng(d)
+    n = k = 6
+    s = 1 + d % 4
+    row_ptr, col, val = cyclic_csr(rng, n, s)
+    bits = np.array([1, 2, 3, 5, 8, 16], dtype=np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = np.array([1, 0, 1, 1, 1, 1], dtype=np.uint8)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    Gd = to_device(G)
+    for scale_mode in MODES:
+        for force_generic in (False, True):
+            out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 42, 7, scale_mode, allow_1bit=True,
+                          force_generic=force_generic, expect_path=0 if force_generic else s)
+            compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 42, 7, scale_mode, out,
+                                tag=f"d={d} mode={scale_mode} generic={force_generic}")
+
+
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_band_width(s):
+    rng = np.random.default_rng(100 + s)
+    n = k = 11 if s <= 5 else 9
+    d = 3000 + 37 * s
+    row_ptr, col, val = cyclic_csr(rng, n, s)
+    bits = rng.integers(2, 13, n).astype(np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = (rng.random(n) < 0.7).astype(np.uint8)
+    G = (rng.standard_normal((k, d)) * 10 ** rng.uniform(-3, 3)).astype(np.float32)
+    out = run_hip(to_device(G), n, k, d, row_ptr, col, val, bits, w, mask, 5, 1 << 40, api.AGC_SCALE_MAXABS,
+                  expect_path=s)
+    compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 5, 1 << 40, api.AGC_SCALE_MAXABS, out,
+                        tag=f"s={s}")
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (1, 7), (7, 1), (5, 9), (9, 5), (33, 20), (64, 64), (200, 17)])
+def test_general_codes(n, k):
+    """Arbitrary sparse codes (empty rows, n != k, repeated use of one partition) take the
+    generic path; the optimally structured interval code of Sec. III-A as well."""
+    rng = np.random.default_rng(n * 1000 + k)
+    d = int(rng.integers(1500, 6000))
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    Gd = to_device(G)
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = (rng.random(n) < 0.6).astype(np.uint8)
+    row_ptr, col, val = random_csr(rng, n, k)
+    out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2)
+    compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2, out, tag="random csr")
+    p = rng.uniform(0.05, 0.6, n)
+    row_ptr, col, val, w2 = api.agc_build_code(n, k, p, bits, 0.3)
+    out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w2, mask, 78, 4, api.AGC_SCALE_MAXABS)
+    compare_with_oracle(G, k, row_ptr, col, val, bits, w2, mask, 78, 4, api.AGC_SCALE_MAXABS, out,
+                        tag="interval code")
+
+
+def test_degenerate_inputs():
+    """All stragglers (estimate exactly 0), everyone arrived, an all-zero coded vector
+    (scale 0), and max-abs coordinates that sit exactly on the top level."""
+    rng = np.random.default_rng(9)
+    n = k = 4
+    d = 2049
+    row_ptr, col, val = cyclic_csr(rng, n, 2)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    G[1] = 0.0
+    G[2] = 0.0          # worker 1 = f(g_1, g_2) is identically zero
+    bits = np.array([2, 4, 8, 3], dtype=np.uint8)
+    w = np.ones(n, dtype=np.float32)
+    Gd = to_device(G)
+    for mask in ([0, 0, 0, 0], [1, 1, 1, 1], [0, 1, 0, 0]):
+        mask = np.array(mask, dtype=np.uint8)
+        out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 1, 2, api.AGC_SCALE_MAXABS)
+        _, o_scales, o_ghat = compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 1, 2,
+                                                  api.AGC_SCALE_MAXABS, out, tag=f"mask={mask}")
+        assert o_scales[1] == 0.0
+        if mask.sum() == 0 or list(mask) == [0, 1, 0, 0]:
+            assert np.all(out[2] == 0)
+    # the coordinate that carries the maximum is coded as +-L, never L+1
+    streams, scales, _ = out
+    csr = O.Csr(row_ptr, col, val, k)
+    for i in (0, 2, 3):
+        f = O.encode(G, csr, i)
+        m = int(np.argmax(np.abs(f)))
+        code = int(O.unpack(streams[i], d, int(bits[i]))[m])
+        assert code & ((1 << (bits[i] - 1)) - 1) == O.levels(int(bits[i]))
+
+
+def test_config2_full_parity():
+    """n = k = 16, s = 3, d = 2^20, bits from the allocator at 4 bits per coordinate."""
+    cfg = I.CONFIGS["n16_d1m"]
+    p = I.straggler_probs(cfg)
+    z_tot = cfg.bits_law[1] * cfg.n
+    bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
+    row_ptr, col, val, w = _config_code(cfg, p, bits)
+    G = I.partial_gradients_numpy(cfg)
+    Gd = to_device(G)
+    for scale_mode in MODES:
+        mask = I.arrival_mask(cfg, p, 0)
+        out = run_hip(Gd, cfg.n, cfg.k, cfg.d, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 0,
+                      scale_mode, expect_path=cfg.s)
+        compare_with_oracle(G, cfg.k, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 0, scale_mode,
+                            out, tag=f"config2 mode={scale_mode}")
+
+
+def test_stage_calls_equal_step_and_are_deterministic():
+    import torch
+    rng = np.random.default_rng(21)
+    n = k = 8
+    d = 5000
+    row_ptr, col, val = cyclic_csr(rng, n, 3)
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = (rng.random(n) < 0.6).astype(np.uint8)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    Gd = to_device(G)
+    a = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 3, 9, api.AGC_SCALE_L2)
+    b = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 3, 9, api.AGC_SCALE_L2)
+    assert all(np.array_equal(x, y) for x, y in zip(a[0], b[0]))
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_L2)
+    ctx.agc_set_code(row_ptr, col, val)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # a non-default stream, passed explicitly
+        ctx.agc_encode_quantize(Gd, bits, 3, 9, codes, scales, stream=side.cuda_stream)
+        ctx.agc_decode(codes, scales, bits, w, mask, ghat, stream=side.cuda_stream)
+    side.synchronize()
+    assert all(np.array_equal(x.cpu().numpy(), y) for x, y in zip(codes, a[0]))
+    assert np.array_equal(ghat.cpu().numpy().view(np.uint32), a[2].view(np.uint32))
+    # different step -> different draws
+    c = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 3, 10, api.AGC_SCALE_L2)
+    assert any(not np.array_equal(x, y) for x, y in zip(a[0], c[0]))
+    ctx.close()
+
+
+def test_argument_errors_are_reported_not_launched():
+    import torch
+    n = k = 4
+    d = 1024
+    ctx = api.Context(n, k, d)
+    bits = np.array([2, 3, 4, 5], dtype=np.uint8)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    G = api.padded_rows(k, d)
+    w = np.ones(n, dtype=np.float32)
+    mask = np.ones(n, dtype=np.uint8)
+    assert ctx.agc_step(G, bits, w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_ESTATE
+    rng = np.random.default_rng(0)
+    ctx.agc_set_code(*cyclic_csr(rng, n, 2))
+    assert ctx.agc_step(G, np.array([1, 3, 4, 5], np.uint8), w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_EBITS
+    assert ctx.agc_step(G, np.array([2, 3, 4, 17], np.uint8), w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_EBITS
+    Gbad = torch.zeros((k, d + 1), dtype=torch.float32, device="cuda")[:, 1:]     # base off by 4 bytes
+    assert ctx.agc_step(Gbad, bits, w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_EALIGN
+    Gld = torch.zeros((k, d + 2), dtype=torch.float32, device="cuda")[:, :d]      # ldg % 4 != 0
+    assert ctx.agc_step(Gld, bits, w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_EALIGN
+    gh_bad = torch.zeros(d + 1, dtype=torch.float32, device="cuda")[1:]
+    assert ctx.agc_step(G, bits, w, mask, 1, 1, codes, scales, gh_bad, check=False) == api.AGC_EALIGN
+    with pytest.raises(api.AgcError) as e:
+        ctx.agc_set_code(np.array([0, 1, 2, 3, 4], np.int32), np.array([0, 1, 2, 9], np.int32),
+                         np.ones(4, np.float32))
+    assert e.value.status == api.AGC_ESHAPE
+    assert ctx.agc_step(G, bits, w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_OK
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+def test_per_kernel_timing_counts_launches():
+    import torch
+    rng = np.random.default_rng(3)
+    n = k = 4
+    d = 1 << 16
+    ctx = api.Context(n, k, d)
+    ctx.agc_set_code(*cyclic_csr(rng, n, 2))
+    bits = np.array([2, 3, 4, 5], dtype=np.uint8)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    G = to_device(rng.standard_normal((k, d)).astype(np.float32))
+    ctx.agc_profile_enable(True)
+    for it in range(150):           # more than the ring holds: the oldest pairs are drained on the way
+        ctx.agc_step(G, bits, np.ones(n, np.float32), np.ones(n, np.uint8), 1, it, codes, scales, ghat)
+    prof = ctx.agc_profile_read()
+    for name in api.KERNEL_NAMES:
+        ms, cnt = prof[name]
+        assert cnt == 150 and 0 < ms < 10_000
+    ctx.agc_profile_enable(False)
+    ctx.agc_step(G, bits, np.ones(n, np.float32), np.ones(n, np.uint8), 1, 0, codes, scales, ghat)
+    torch.cuda.synchronize()
+    assert all(c == 0 for _, c in ctx.agc_profile_read().values())
+    ctx.close()
+
+
+def test_montecarlo_unbiased_on_gpu():
+    """1000 GPU steps on the tiny configuration with fresh arrivals: projections of the mean
+    error on fixed directions stay within 3 standard errors of zero."""
+    import torch
+    cfg = I.CONFIGS["tiny"]
+    p, bits = I.straggler_probs(cfg), I.random_bits(cfg)
+    row_ptr, col, val, w = _config_code(cfg, p, bits)
+    G = I.partial_gradients_numpy(cfg)
+    Gd = to_device(G)
+    g = torch.from_numpy(G.astype(np.float64).sum(axis=0)).cuda()
+    rng = np.random.default_rng(77)
+    dirs = rng.standard_normal((8, cfg.d))
+    dirs /= np.linalg.norm(dirs, axis=1, keepdims=True)
+    dirs_d = torch.from_numpy(dirs).cuda()
+    ctx = api.Context(cfg.n, cfg.k, cfg.d)
+    ctx.agc_set_code(row_ptr, col, val)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    T = cfg.iters
+    proj = torch.zeros((T, 8), dtype=torch.float64, device="cuda")
+    for t in range(T):
+        ctx.agc_step(Gd, bits, w, I.arrival_mask(cfg, p, t), cfg.philox_seed, t, codes, scales, ghat)
+        proj[t] = dirs_d @ (ghat.double() - g)
+    proj = proj.cpu().numpy()
+    z = proj.mean(axis=0) / (proj.std(axis=0, ddof=1) / np.sqrt(T))
+    assert np.all(np.abs(z) < 3.0), z
+    ctx.close()

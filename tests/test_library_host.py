@@ -1,0 +1,141 @@
+"""CPU-only checks of the built library: it loads, exports every symbol the header declares,
+and its host-side design routines agree with the oracle's binary64 versions."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import agc_oracle as O
+from oracle import design as D
+from paper_2605_15890_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "agc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(agc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = api.load()
+    names = _declared_symbols()
+    assert len(names) >= 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(api.EXPORTS) == names
+
+
+def test_code_bytes_matches_payload_definition():
+    for d in (1, 127, 128, 129, 4096, 25_600_000):
+        for b in range(1, 17):
+            assert api.agc_code_bytes(d, b) == -(-d // 128) * 16 * b == O.code_bytes(d, b)
+    assert api.agc_code_bytes(0, 4) == 0 and api.agc_code_bytes(10, 17) == 0
+
+
+def test_create_rejects_bad_shapes_without_touching_the_gpu():
+    lib = api.load()
+    h = ctypes.c_void_p()
+    for n, k, d in [(0, 4, 16), (257, 4, 16), (4, 0, 16), (4, 4, 0), (4, 4, (1 << 33) + 1)]:
+        assert lib.agc_create(ctypes.byref(h), n, k, d, None) == api.AGC_ESHAPE
+        assert not h.value
+    assert lib.agc_create(None, 4, 4, 16, None) == api.AGC_EINVAL
+    bad = api.AgcOpts(7, 0, 0, (ctypes.c_int * 5)())
+    assert lib.agc_create(ctypes.byref(h), 4, 4, 16, ctypes.byref(bad)) == api.AGC_EINVAL
+
+
+def test_phi_coef_balanced():
+    rng = np.random.default_rng(0)
+    p = rng.uniform(0.05, 0.6, 16)
+    assert api.agc_phi_coef_balanced(p, 64) == pytest.approx(D.phi_coef_balanced(p, 64), rel=1e-14)
+
+
+def test_dp_allocator_is_optimal():
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        n = int(rng.integers(2, 6))
+        p = rng.uniform(0.02, 0.7, n)
+        z_total = 2 * n + int(rng.integers(0, 9))
+        pc = 10 ** rng.uniform(-2, 2)
+        bits = api.agc_alloc_bits_dp(p, pc, z_total, 2, 8)
+        assert bits.sum() == z_total and bits.min() >= 2 and bits.max() <= 8
+        r_bf, f_bf = D.alloc_bruteforce(p, pc, z_total - 2 * n, 6)
+        assert api.agc_alloc_objective(p, pc, bits) == pytest.approx(f_bf, rel=1e-12)
+        assert D.objective(p, bits.astype(int) - 2, pc) == pytest.approx(f_bf, rel=1e-12)
+
+
+def test_low_complexity_allocator_near_optimal_and_feasible():
+    rng = np.random.default_rng(2)
+    worst = 1.0
+    for trial in range(40):
+        n = int(rng.integers(3, 65))
+        p = rng.uniform(0.05, 0.6, n)
+        z_total = 2 * n + int(rng.integers(1, 4 * n))
+        pc = api.agc_phi_coef_balanced(p, z_total) if trial % 2 else 10 ** rng.uniform(-1, 2)
+        bits = api.agc_alloc_bits(p, pc, z_total, 2, 8)
+        assert bits.sum() == z_total and bits.min() >= 2 and bits.max() <= 8
+        f = api.agc_alloc_objective(p, pc, bits)
+        f_dp = api.agc_alloc_objective(p, pc, api.agc_alloc_bits_dp(p, pc, z_total, 2, 8))
+        assert f <= f_dp * (1 + 1e-12)
+        worst = min(worst, f / f_dp)
+        if n <= 10:   # the oracle's own reading of Algorithm 1 reaches the same utility
+            _, f_or = D.alloc_lowcomplexity(p, pc, z_total - 2 * n, 6)
+            assert f == pytest.approx(f_or, rel=1e-9)
+    assert worst >= 1 - 1e-3
+
+
+def test_allocator_argument_errors():
+    p = np.array([0.1, 0.2])
+    with pytest.raises(api.AgcError) as e:
+        api.agc_alloc_bits(p, 1.0, 3, 2, 8)          # below n * z_min
+    assert e.value.status == api.AGC_EBITS
+    with pytest.raises(api.AgcError):
+        api.agc_alloc_bits(p, 1.0, 17, 2, 8)         # above n * z_max
+    with pytest.raises(api.AgcError):
+        api.agc_alloc_bits(p, 1.0, 6, 1, 8)          # z_min below the paper's minimum of 2
+    with pytest.raises(api.AgcError):
+        api.agc_alloc_bits(np.array([0.1, 1.0]), 1.0, 6, 2, 8)
+
+
+@pytest.mark.parametrize("n,k", [(3, 3), (5, 8), (8, 5), (64, 64)])
+def test_interval_code_matches_oracle(n, k):
+    rng = np.random.default_rng(n + k)
+    p = rng.uniform(0.05, 0.6, n)
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    pc = 0.3
+    row_ptr, col, val, w = api.agc_build_code(n, k, p, bits, pc)
+    alpha = D.interval_code(D.row_targets(D.c_weights(p, bits, pc), k), k)
+    dense = O.Csr(row_ptr, col, val, k).dense()
+    keep = alpha > 1e-9          # entries at rounding level may or may not be stored
+    assert np.allclose(dense, alpha, atol=1e-6)
+    assert np.all(dense[keep] > 0)
+    assert len(col) <= n + k - 1 + 2
+    assert np.allclose(w, 1 / (1 - p), rtol=1e-6)
+    for i in range(n):   # columns ascending inside a row
+        c = col[row_ptr[i]:row_ptr[i + 1]]
+        assert np.all(np.diff(c) > 0)
+    ok, res = api.agc_check_unbiased(k, row_ptr, col, val, w, p, 1e-5)
+    assert ok and res < 1e-5
+    val_bad = val.copy()
+    val_bad[0] *= 1.5
+    ok, res = api.agc_check_unbiased(k, row_ptr, col, val_bad, w, p, 1e-5)
+    assert not ok and res > 1e-3
+
+
+def test_cyclic_code_matches_oracle():
+    rng = np.random.default_rng(5)
+    for n, s in [(4, 2), (16, 3), (64, 4), (5, 5), (6, 1)]:
+        p = rng.uniform(0.05, 0.6, n)
+        bits = rng.integers(2, 9, n).astype(np.uint8)
+        row_ptr, col, val, w = api.agc_build_cyclic_code(n, n, s, p, bits, 0.2)
+        alpha, supp = D.cyclic_code(D.c_weights(p, bits, 0.2), n, s)
+        assert np.array_equal(row_ptr, np.arange(n + 1) * s)
+        assert np.array_equal(col.reshape(n, s), np.array(supp))
+        assert np.allclose(val.reshape(n, s), [[alpha[i, j] for j in supp[i]] for i in range(n)], rtol=1e-6)
+        ok, res = api.agc_check_unbiased(n, row_ptr, col, val, w, p, 1e-5)
+        assert ok
+    with pytest.raises(api.AgcError):
+        api.agc_build_cyclic_code(4, 5, 2, [0.1] * 4, [2] * 4, 0.2)
