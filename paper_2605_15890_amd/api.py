@@ -50,6 +50,14 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_15890_amd.build`; "
                            "there is no fallback path")
+    # The library needs the HIP runtime (libamdhip64.so.7).  PyTorch ships its own copy and the
+    # device memory and streams this binding passes down come from that copy, so it has to be
+    # in the process first: the loader then binds libagc.so to it by soname instead of pulling
+    # a second runtime from the system ROCm directory.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(LIB_PATH)
     L.agc_create.argtypes = [C.POINTER(_vp), C.c_int, C.c_int, C.c_int64, C.POINTER(AgcOpts)]
     L.agc_create.restype = C.c_int
@@ -198,7 +206,7 @@ class Context:
         h = _vp()
         st = self.lib.agc_create(C.byref(h), self.n, self.k, self.d, C.byref(opts))
         if st != AGC_OK:
-            raise AgcError(st, "agc_create")
+            raise AgcError(st, "agc_create: " + self.lib.agc_last_error(None).decode())
         self.h = h
 
     def close(self):

@@ -22,8 +22,27 @@ FLAGS = [
 ]
 
 
+def hip_runtime_link_flags():
+    """The process that loads libagc.so already holds PyTorch's own copy of the HIP runtime
+    (its device memory and streams come from there), so the library must bind to that copy and
+    not bring a second runtime into the process: link against the libamdhip64.so that ships
+    inside the torch package, with the system ROCm directory as a fallback search path."""
+    flags = ["-no-hip-rt"]
+    try:
+        import importlib.util
+        spec = importlib.util.find_spec("torch")
+        tlib = os.path.join(os.path.dirname(spec.origin), "lib") if spec and spec.origin else None
+    except Exception:
+        tlib = None
+    if tlib and os.path.exists(os.path.join(tlib, "libamdhip64.so")):
+        flags += ["-L" + tlib, "-Wl,-rpath," + tlib]
+    flags += ["-L/opt/rocm/lib", "-Wl,-rpath,/opt/rocm/lib", "-lamdhip64"]
+    return flags
+
+
 def build(verbose: bool = True, extra=()) -> str:
-    cmd = [HIPCC, *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    cmd = [HIPCC, *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB,
+           *hip_runtime_link_flags()]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -47,9 +47,12 @@ struct agc_ctx {
 
 namespace {
 
+thread_local std::string g_err;  // failures that have no context to hang on (agc_create)
+
 agc_status fail(agc_ctx* ctx, agc_status st, const std::string& msg)
 {
     if (ctx) ctx->err = msg;
+    else g_err = msg;
     return st;
 }
 
@@ -156,7 +159,7 @@ int64_t agc_code_bytes(int64_t d, int bits)
     return ((d + 127) / 128) * 16 * (int64_t)bits;
 }
 
-const char* agc_last_error(const agc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+const char* agc_last_error(const agc_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
 agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* opts)
 {
@@ -178,15 +181,15 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     c->k = k;
     c->d = d;
     c->opts = o;
-    if (hipGetDevice(&c->device) != hipSuccess) {
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) {
         delete c;
-        return AGC_EHIP;
+        return hip_fail(nullptr, e, "hipGetDevice");
     }
     const int64_t nblocks = (d + 255) / 256;
     c->ws.nseg = (nblocks + 3) / 4;
     c->ws.ngroup = (c->ws.nseg + 63) / 64;
     c->ws.nsuper = (c->ws.ngroup + 63) / 64;
-    hipError_t e = hipSuccess;
     if (o.scale_mode == AGC_SCALE_MAXABS) {
         e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nseg * n);
     } else {
@@ -197,7 +200,8 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     if (e == hipSuccess) e = dev_alloc(&c->ws.inv16, (size_t)n);
     if (e != hipSuccess) {
         agc_destroy(c);
-        return e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP;
+        return fail(nullptr, e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP,
+                    std::string("workspace allocation: ") + hipGetErrorString(e));
     }
     *out = c;
     return AGC_OK;
