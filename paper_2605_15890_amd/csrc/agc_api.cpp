@@ -197,7 +197,8 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
         if (e == hipSuccess) e = dev_alloc(&c->ws.group_sq, (size_t)c->ws.ngroup * n);
         if (e == hipSuccess) e = dev_alloc(&c->ws.super_sq, (size_t)c->ws.nsuper * n);
     }
-    if (e == hipSuccess) e = dev_alloc(&c->ws.inv16, (size_t)n);
+    if (e == hipSuccess) e = dev_alloc(&c->ws.wq, (size_t)n);
+    if (e == hipSuccess) e = dev_alloc(&c->ws.wd, (size_t)n);
     if (e != hipSuccess) {
         agc_destroy(c);
         return fail(nullptr, e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP,
@@ -215,7 +216,8 @@ void agc_destroy(agc_ctx* c)
     if (c->ws.part_sq) (void)hipFree(c->ws.part_sq);
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
-    if (c->ws.inv16) (void)hipFree(c->ws.inv16);
+    if (c->ws.wq) (void)hipFree(c->ws.wq);
+    if (c->ws.wd) (void)hipFree(c->ws.wd);
     for (auto& ring : c->events)
         for (auto& ep : ring) {
             if (ep.beg) (void)hipEventDestroy(ep.beg);
@@ -286,10 +288,8 @@ agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const ui
     if (st != AGC_OK) return st;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     const agc::CodeDev code = code_dev(c);
-    agc::PerWorkerBits pb{};
     agc::QuantStreams qs{};
     for (int i = 0; i < c->n; ++i) {
-        pb.bits[i] = bits[i];
         qs.bits[i] = bits[i];
         qs.codes[i] = codes[i];
     }
@@ -304,14 +304,14 @@ agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const ui
     {
         KernelTimer t{c, 1, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, pb, c->ws, scales, stream);
+        e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, qs, c->ws, scales, stream);
         if (e != hipSuccess) return hip_fail(c, e, "scale finalize launch");
         if ((st = t.end()) != AGC_OK) return st;
     }
     {
         KernelTimer t{c, 2, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, qs, stream);
+        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, stream);
         if (e != hipSuccess) return hip_fail(c, e, "quantize launch");
         if ((st = t.end()) != AGC_OK) return st;
     }
@@ -330,15 +330,16 @@ agc_status agc_decode(agc_ctx* c, void* const* codes, const float* scales, const
     if (st != AGC_OK) return st;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     agc::DecodeStreams ds{};
+    int n_arrived = 0;
     for (int i = 0; i < c->n; ++i) {
         ds.codes[i] = codes[i];
         ds.w[i] = w[i];
         ds.bits[i] = bits[i];
-        ds.mask[i] = mask[i] ? 1 : 0;
+        ds.slot[i] = mask[i] ? (uint16_t)n_arrived++ : (uint16_t)0xFFFF;
     }
     KernelTimer t{c, 3, stream};
     if ((st = t.begin()) != AGC_OK) return st;
-    hipError_t e = agc::launch_decode(c->n, c->d, ds, scales, ghat, stream);
+    hipError_t e = agc::launch_decode(c->n, n_arrived, c->d, ds, scales, c->ws, ghat, stream);
     if (e != hipSuccess) return hip_fail(c, e, "decode launch");
     return t.end();
 }

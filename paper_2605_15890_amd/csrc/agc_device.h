@@ -1,5 +1,5 @@
-// Device-side building blocks of the gfx950 kernels: Philox4x32-10, wave reductions and the
-// two encode drivers (cyclic-band register ring, generic CSR gather).
+// Device-side building blocks of the gfx950 kernels: Philox4x32-10, DPP wave reductions and
+// the two encode drivers (cyclic-band register ring, generic CSR gather).
 //
 // Thread geometry shared by the scale pass and the encode+quantize+pack pass: a wave covers
 // one block of 256 consecutive coordinates, lane l owning the float4 at coordinates 4l..4l+3;
@@ -26,7 +26,8 @@ constexpr int kMaxBand = 8;     // largest replication factor served by the regi
 // ---------------------------------------------------------------------------------------
 // Philox4x32 with ten rounds (Salmon et al., SC'11).  Round: the two 32x32->64 products of
 // counter words 0 and 2 with fixed odd multipliers; high halves are mixed with words 1 and 3
-// and the round key; the key advances by Weyl constants.
+// and the round key; the key advances by Weyl constants.  On gfx950 the wide product is one
+// full-rate v_mad_u64_u32, so a block costs about 60 vector instructions.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])
@@ -51,51 +52,93 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 // ---------------------------------------------------------------------------------------
-// wave-wide reductions (all lanes receive the result)
+// wave-wide reductions on the DPP cross-lane network (no LDS traffic)
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_max_nonneg(float v)
+constexpr int kDppQuadSwap1 = 0xB1;     // quad_perm [1,0,3,2]: partner l ^ 1
+constexpr int kDppQuadSwap2 = 0x4E;     // quad_perm [2,3,0,1]: partner l ^ 2
+constexpr int kDppHalfMirror = 0x141;   // l -> 7 - l within 8 lanes: a partner in the other quad
+constexpr int kDppRowMirror = 0x140;    // l -> 15 - l within 16 lanes: a partner in the other half
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
 {
-    // non-negative floats order like their bit patterns
-#pragma unroll
-    for (int h = 1; h < kWave; h <<= 1) v = fmaxf(v, __shfl_xor(v, h, kWave));
-    return v;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// exchange-add over lanes at distances 1,2,4,8,16,32: the second level of the norm's tree
+// maximum over the wave of non-negative floats, returned as a wave-uniform bit pattern
+// (non-negative floats order like their bit patterns)
+__device__ __forceinline__ uint32_t wave_max_nonneg_bits(float x)
+{
+    uint32_t v = __float_as_uint(x);
+    v = max(v, dpp_u32<kDppQuadSwap1>(v));
+    v = max(v, dpp_u32<kDppQuadSwap2>(v));
+    v = max(v, dpp_u32<kDppHalfMirror>(v));
+    v = max(v, dpp_u32<kDppRowMirror>(v));  // every 16-lane row now holds its maximum
+    const uint32_t r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    const uint32_t r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    return max(max(r0, r1), max(r2, r3));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = dpp_u32<CTRL>((uint32_t)b), hi = dpp_u32<CTRL>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)b, lane);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(b >> 32), lane);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// Exchange-add over lanes at distances 1,2,4,8,16,32 (second level of the norm's tree),
+// result wave-uniform.  After the steps at distance 1 and 2 every quad is uniform, so the
+// mirror partners used for distances 4 and 8 hold exactly the value of lane l^4 and l^8; after
+// distance 8 every 16-lane row is uniform and the last two steps are (r0+r1)+(r2+r3) on the
+// four row values, which is what lanes of rows 0 and 1 compute in the exchange (rows 2 and 3
+// compute the commuted, identical sum).
 __device__ __forceinline__ double wave_butterfly_add(double v)
 {
-#pragma unroll
-    for (int h = 1; h < kWave; h <<= 1) v = v + __shfl_xor(v, h, kWave);
-    return v;
+    v = v + dpp_f64<kDppQuadSwap1>(v);
+    v = v + dpp_f64<kDppQuadSwap2>(v);
+    v = v + dpp_f64<kDppHalfMirror>(v);
+    v = v + dpp_f64<kDppRowMirror>(v);
+    const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16);
+    const double r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
+    const double a = r0 + r1, b = r2 + r3;
+    return a + b;
 }
 
 // ---------------------------------------------------------------------------------------
-// loads of one lane's float4 of row `row`
+// loads of one lane's float4
 // ---------------------------------------------------------------------------------------
 struct LaneCoords {
-    int64_t m0;         // first coordinate of the lane
-    int nvalid;         // how many of m0..m0+3 are < d (0..4)
-    bool wave_partial;  // wave-uniform: some lane of this wave has 0 < nvalid < 4
+    int64_t m_load;    // first coordinate the lane loads from (clamped into the row for lanes past d)
+    int nvalid;        // how many of the lane's four coordinates are < d (0..4)
+    bool wave_ragged;  // wave-uniform: some lane of this wave has nvalid < 4
 };
 
 __device__ __forceinline__ LaneCoords lane_coords(int64_t m0, int64_t d)
 {
     LaneCoords lc;
-    lc.m0 = m0;
     const int64_t left = d - m0;
     lc.nvalid = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
-    lc.wave_partial = __any(lc.nvalid > 0 && lc.nvalid < 4) != 0;
+    lc.m_load = left > 0 ? m0 : ((d - 1) & ~(int64_t)3);
+    lc.wave_ragged = __any(lc.nvalid < 4) != 0;
     return lc;
 }
 
-__device__ __forceinline__ float4 load_row4(const float* __restrict__ G, int64_t ldg, int row,
-                                            const LaneCoords& lc)
+// every lane loads (lanes past d re-read the last float4 of the row and are zeroed), so the
+// load needs no per-lane predicate; coordinates >= d count as 0
+__device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const LaneCoords& lc)
 {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (lc.nvalid > 0) {
-        v = *reinterpret_cast<const float4*>(G + (int64_t)row * ldg + lc.m0);
-    }
-    if (lc.wave_partial) {  // the one float4 that straddles d: coordinates >= d count as 0
+    float4 v = *reinterpret_cast<const float4*>(row + lc.m_load);
+    if (lc.wave_ragged) {
+        if (lc.nvalid < 1) v.x = 0.f;
         if (lc.nvalid < 2) v.y = 0.f;
         if (lc.nvalid < 3) v.z = 0.f;
         if (lc.nvalid < 4) v.w = 0.f;
@@ -115,30 +158,74 @@ __device__ __forceinline__ float4 fma4(float a, const float4& g, const float4& c
 // ---------------------------------------------------------------------------------------
 // Encode driver 1: cyclic band.  n == k, worker i stores columns (i+u) mod k, u = 0..S-1.
 // Rows stream once through a ring of R = S + P float4 registers (P rows of prefetch); worker
-// i is formed when row i+S-1 has arrived; the last S-1 workers wrap around and re-read rows
-// 0..S-2.  R is even so that the parity of the worker handled at each unrolled position is
-// known at compile time (the quantizer shares one Philox block between workers 2q and 2q+1).
-// The epilogue is called for workers 0..n-1 in ascending order.
+// i is formed when row i+S-1 has arrived.  The first S-1 rows are kept in a register stash
+// for the last S-1 workers, which wrap around, so every element of G is read exactly once.
+// R is even so that the parity of the worker handled at each unrolled position is known at
+// compile time (the quantizer shares one Philox block between workers 2q and 2q+1).  The
+// epilogue is called for workers 0..n-1 in ascending order.
 // ---------------------------------------------------------------------------------------
 template <int S>
 struct RingShape {
     static constexpr int P = ((S + 4) & 1) ? 5 : 4;
     static constexpr int R = S + P;
+    static constexpr int NSTASH = S > 1 ? S - 1 : 1;
 };
 
-template <int S, int r, class Epi>
-__device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R], const float* __restrict__ G,
+// value select (the operands are read before the choice, so the choice is between registers)
+__device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)
+{
+    return make_float4(c ? a.x : b.x, c ? a.y : b.y, c ? a.z : b.z, c ? a.w : b.w);
+}
+
+// stash helpers with compile-time indices (so the stash stays in registers)
+template <int S, int... Us>
+__device__ __forceinline__ float4 stash_pick(const float4 (&stash)[RingShape<S>::NSTASH], int idx,
+                                             std::integer_sequence<int, Us...>)
+{
+    float4 v = stash[0];
+    ((v = sel4(idx == Us + 1, stash[(Us + 1) < RingShape<S>::NSTASH ? (Us + 1) : 0], v)), ...);
+    return v;
+}
+
+template <int S, int r, int... Us>
+__device__ __forceinline__ void stash_fill(float4 (&stash)[RingShape<S>::NSTASH],
+                                           const float4 (&ring)[RingShape<S>::R],
+                                           std::integer_sequence<int, Us...>)
+{
+    constexpr int R = RingShape<S>::R;
+    ((stash[Us] = ring[(r + R - (S - 1) + Us) % R]), ...);
+}
+
+// One row arrival.  STEADY rounds are straight-line code: every prefetch is issued (past the
+// last row the last row is re-read, a cache hit whose value is never used), every worker index
+// is valid and no wrapped row is involved, so the compiler can count outstanding loads exactly
+// and let P of them stay in flight.  The first round and the last one or two (GENERAL) carry
+// the conditions: workers that do not exist yet, the stash fill, the wrapped rows.
+template <int S, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
+                                          float4 (&stash)[RingShape<S>::NSTASH],
+                                          const float*& next_row, const float* last_row,
                                           int64_t ldg, int k, const float* __restrict__ bval,
-                                          const LaneCoords& lc, int j0, int steps, Epi& epi)
+                                          const LaneCoords& lc, int j0, Epi& epi)
 {
     constexpr int P = RingShape<S>::P;
     constexpr int R = RingShape<S>::R;
     const int j = j0 + r;
-    int jn = j + P;  // prefetch; past the end the last row is re-read (harmless, cached)
-    jn = jn < steps ? jn : steps - 1;
-    ring[(r + P) % R] = load_row4(G, ldg, jn < k ? jn : jn - k, lc);
+    if (STEADY) {
+        ring[(r + P) % R] = load_row4(next_row < last_row ? next_row : last_row, lc);
+        next_row += ldg;
+    } else {
+        if (j + P < k) {  // prefetch the row that arrives P steps from now
+            ring[(r + P) % R] = load_row4(next_row, lc);
+            next_row += ldg;
+        }
+        if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
+            ring[r] = stash_pick<S>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
+    }
     const int i = j - (S - 1);
-    if (i >= 0 && i < k) {
+    if (STEADY || (i >= 0 && i < k)) {
+        if (!STEADY && S > 1 && i == 0)
+            stash_fill<S, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
         const float* bv = bval + (int64_t)i * S;
         float4 f = mul4(bv[0], ring[(r + R - (S - 1)) % R]);
 #pragma unroll
@@ -147,13 +234,15 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R], const
     }
 }
 
-template <int S, class Epi, int... Rs>
-__device__ __forceinline__ void ring_round(float4 (&ring)[RingShape<S>::R], const float* __restrict__ G,
+template <int S, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void ring_round(float4 (&ring)[RingShape<S>::R],
+                                           float4 (&stash)[RingShape<S>::NSTASH],
+                                           const float*& next_row, const float* last_row,
                                            int64_t ldg, int k, const float* __restrict__ bval,
-                                           const LaneCoords& lc, int j0, int steps, Epi& epi,
+                                           const LaneCoords& lc, int j0, Epi& epi,
                                            std::integer_sequence<int, Rs...>)
 {
-    (ring_step<S, Rs>(ring, G, ldg, k, bval, lc, j0, steps, epi), ...);
+    (ring_step<S, Rs, STEADY>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi), ...);
 }
 
 template <int S, class Epi>
@@ -164,17 +253,28 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
     constexpr int P = RingShape<S>::P;
     constexpr int R = RingShape<S>::R;
     static_assert(R % 2 == 0, "ring length must be even");
+    constexpr auto seq = std::make_integer_sequence<int, R>{};
     const int steps = k + S - 1;  // row arrivals, the last S-1 being the wrapped rows
     float4 ring[R];
+    float4 stash[RingShape<S>::NSTASH];
+    const float* next_row = G;
+    const float* last_row = G + (int64_t)(k - 1) * ldg;
+#pragma unroll
+    for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    stash[0] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int r = 0; r < P; ++r) {
-        const int j = r < steps ? r : steps - 1;
-        ring[r] = load_row4(G, ldg, j < k ? j : j - k, lc);
+        if (r < k) {
+            ring[r] = load_row4(next_row, lc);
+            next_row += ldg;
+        }
     }
-#pragma unroll
-    for (int r = P; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j0 = 0; j0 < steps; j0 += R)
-        ring_round<S>(ring, G, ldg, k, bval, lc, j0, steps, epi, std::make_integer_sequence<int, R>{});
+    int j0 = 0;
+    ring_round<S, false>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
+    for (j0 = R; j0 + R - 1 < k; j0 += R)
+        ring_round<S, true>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
+    for (; j0 < steps; j0 += R)
+        ring_round<S, false>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -193,8 +293,9 @@ __device__ __forceinline__ float4 encode_gather_one(const float* __restrict__ G,
     const int e0 = B.row_ptr[i], e1 = B.row_ptr[i + 1];
     float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e0 < e1) {
-        f = mul4(B.val[e0], load_row4(G, ldg, B.col[e0], lc));
-        for (int e = e0 + 1; e < e1; ++e) f = fma4(B.val[e], load_row4(G, ldg, B.col[e], lc), f);
+        f = mul4(B.val[e0], load_row4(G + (int64_t)B.col[e0] * ldg, lc));
+        for (int e = e0 + 1; e < e1; ++e)
+            f = fma4(B.val[e], load_row4(G + (int64_t)B.col[e] * ldg, lc), f);
     }
     return f;
 }

@@ -17,44 +17,56 @@ struct CodeDev {          // the code matrix B on the device
     int band;             // 0: generic CSR; s>0: cyclic band with s entries per row
 };
 
+// what the quantize pass needs to know about worker i, read with one scalar 16-byte load
+struct WorkerQ {
+    float inv16;          // L_i * 2^16 / scale_i (2^15 / scale_i for a one-bit worker)
+    uint32_t bits;
+    void* codes;          // packed stream of the worker
+};
+
+// one arrived worker as the decode pass sees it
+struct WorkerD {
+    const void* codes;
+    float coef;           // w_i * scale_i / L_i
+    uint32_t bits;
+};
+
 struct Workspace {
-    float* part_max;      // [nseg][n]   per-segment max |f_i|            (max-abs scale)
-    double* part_sq;      // [nseg][n]   per-segment sum of squares       (Euclidean scale)
+    uint32_t* part_max;   // [n][nseg]   per-segment max |f_i| as bit patterns  (max-abs scale)
+    double* part_sq;      // [n][nseg]   per-segment sum of squares             (Euclidean scale)
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
-    float* inv16;         // [n]         L_i * 2^16 / scale_i
+    WorkerQ* wq;          // [n]  written by the scale finalize
+    WorkerD* wd;          // [n]  arrived workers, compacted, written by the decode prologue
     int64_t nseg, ngroup, nsuper;
 };
 
-struct PerWorkerBits {
-    uint8_t bits[kArgWorkers];
-};
-
-struct QuantStreams {
+struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];
     uint8_t bits[kArgWorkers];
 };
 
-struct DecodeStreams {
+struct DecodeStreams {     // host arrays of the decode call, as kernel arguments of its prologue
     const void* codes[kArgWorkers];
     float w[kArgWorkers];
     uint8_t bits[kArgWorkers];
-    uint8_t mask[kArgWorkers];
+    uint16_t slot[kArgWorkers];  // position among the arrived workers, 0xFFFF for a straggler
 };
 
 // K1: per-segment partials of every worker's scale.  scale_mode: 0 Euclidean, 1 max-abs.
 hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t d,
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream);
-// K1f: partials -> scales[n] and inv16[n].
-hipError_t launch_scale_finalize(int n, int scale_mode, const PerWorkerBits& bits,
+// K1f: partials -> scales[n] and the per-worker table of the quantize pass.
+hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
                                  const Workspace& ws, float* scales, hipStream_t stream);
 // K2: fused encode + stochastic quantize + bit-pack.
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           const QuantStreams& out, hipStream_t stream);
-// K3: masked dequantize + weighted sum.
-hipError_t launch_decode(int n, int64_t d, const DecodeStreams& in, const float* scales,
-                         float* ghat, hipStream_t stream);
+                           hipStream_t stream);
+// K3: table of the arrived workers (a one-workgroup prologue), then masked dequantize +
+// weighted sum.
+hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
+                         const float* scales, const Workspace& ws, float* ghat, hipStream_t stream);
 
 }  // namespace agc

@@ -2,14 +2,18 @@
 //
 //   k_scale_pass      worker side, pass 1: stream G once, form f_i = sum_j a_ij g_j in registers
 //                     (Sec. II-A) and reduce each worker's scale per 1024-coordinate segment
-//   k_scale_finalize  fixed-order reduction of the segment partials -> scale_i, inv16_i
+//   k_scale_finalize  fixed-order reduction of the segment partials -> scale_i and the
+//                     per-worker table (inv16_i, b_i, stream pointer) of the next pass
 //   k_quantize        worker side, pass 2: stream G once more, re-form f_i, stochastic rounding
 //                     on the grid {0,1/L,..,1} (Sec. II-B) with Philox draws, variable-width
 //                     bit-packing, coalesced stores of the payload
+//   k_decode_table    master side prologue: table of the arrived workers with their weights
 //   k_decode          master side: masked dequantize + weighted sum (Sec. II-A aggregation)
 //
-// All four are bandwidth/ALU streaming kernels; there is no dense contraction on this path,
-// hence no MFMA.
+// All of them are bandwidth/ALU streaming kernels; there is no dense contraction on this
+// path, hence no MFMA.  Per-worker parameters are read with scalar loads from small device
+// tables, never with vector loads, so that waiting for them does not drain the queue of
+// outstanding row loads.
 #include "agc_device.h"
 #include "agc_kernels.h"
 
@@ -18,25 +22,28 @@ namespace agc {
 // =======================================================================================
 // K1  scale pass
 // =======================================================================================
+// Pointers that the kernels only read are separate __restrict__ kernel parameters: that is
+// what lets the compiler keep wave-uniform reads (code coefficients, per-worker tables) on the
+// scalar unit even though the same kernel stores through other pointers.
 struct ScaleArgs {
-    const float* G;
     int64_t ldg;
     int n, k;
     int64_t d;
-    CodeDev code;
-    Workspace ws;
+    int64_t nseg;
+    uint32_t* part_max;
+    double* part_sq;
 };
 
 // epilogue for the largest-magnitude scale: exact and order-free
 struct EpiMaxAbs {
-    float* acc;  // this wave's LDS slice [n]
+    uint32_t* acc;  // this wave's LDS slice [n], bit patterns of non-negative floats
     int lane;
     template <bool EVEN>
     __device__ __forceinline__ void worker(int i, const float4& f)
     {
-        float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
-        a = wave_max_nonneg(a);
-        if (lane == 0) acc[i] = fmaxf(acc[i], a);
+        const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+        const uint32_t m = wave_max_nonneg_bits(a);
+        if (lane == 0) atomicMax(&acc[i], m);
     }
 };
 
@@ -51,13 +58,17 @@ struct EpiSumSq {
         const double x0 = f.x, x1 = f.y, x2 = f.z, x3 = f.w;
         const double s01 = x0 * x0 + x1 * x1;
         const double s23 = x2 * x2 + x3 * x3;
-        double q = wave_butterfly_add(s01 + s23);
+        const double q = wave_butterfly_add(s01 + s23);
         if (lane == 0) acc[i] = acc[i] + q;
     }
 };
 
 template <int S, int MODE>
-__global__ __launch_bounds__(kWgThreads) void k_scale_pass(ScaleArgs a)
+__global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restrict__ G,
+                                                           const int* __restrict__ row_ptr,
+                                                           const int* __restrict__ col,
+                                                           const float* __restrict__ val,
+                                                           ScaleArgs a)
 {
     __shared__ double lds_acc[kWavesPerWg][kMaxWorkers];
     const int wave = threadIdx.x / kWave;
@@ -65,44 +76,49 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(ScaleArgs a)
     const int64_t seg = (int64_t)blockIdx.x * kWavesPerWg + wave;
 
     double* accd = lds_acc[wave];
-    float* accf = reinterpret_cast<float*>(lds_acc[wave]);
+    uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
     for (int i = lane; i < a.n; i += kWave) {
         if (MODE == 0) accd[i] = 0.0;
-        else accf[i] = 0.f;
+        else accu[i] = 0u;
     }
     __syncthreads();
 
-    if (seg < a.ws.nseg) {
+    if (seg < a.nseg) {
         for (int blk = 0; blk < kSegBlocks; ++blk) {
             const int64_t base = (seg * kSegBlocks + blk) * (int64_t)kBlockCoords;
             if (base >= a.d) break;
             const LaneCoords lc = lane_coords(base + 4 * lane, a.d);
             if (MODE == 0) {
                 EpiSumSq epi{accd, lane};
-                if constexpr (S > 0) encode_ring<S>(a.G, a.ldg, a.k, a.code.val, lc, epi);
-                else encode_gather(a.G, a.ldg, a.n, CsrView{a.code.row_ptr, a.code.col, a.code.val}, lc, epi);
+                if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
+                else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
             } else {
-                EpiMaxAbs epi{accf, lane};
-                if constexpr (S > 0) encode_ring<S>(a.G, a.ldg, a.k, a.code.val, lc, epi);
-                else encode_gather(a.G, a.ldg, a.n, CsrView{a.code.row_ptr, a.code.col, a.code.val}, lc, epi);
+                EpiMaxAbs epi{accu, lane};
+                if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
+                else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
             }
         }
     }
     __syncthreads();
-    if (seg < a.ws.nseg) {
+    if (seg < a.nseg) {
         for (int i = lane; i < a.n; i += kWave) {
-            if (MODE == 0) a.ws.part_sq[seg * a.n + i] = accd[i];
-            else a.ws.part_max[seg * a.n + i] = accf[i];
+            if (MODE == 0) a.part_sq[(int64_t)i * a.nseg + seg] = accd[i];
+            else a.part_max[(int64_t)i * a.nseg + seg] = accu[i];
         }
     }
 }
 
 template <int S>
-static hipError_t launch_scale_pass_s(const ScaleArgs& a, int scale_mode, hipStream_t stream)
+static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const ScaleArgs& a,
+                                      int scale_mode, hipStream_t stream)
 {
-    const unsigned grid = (unsigned)((a.ws.nseg + kWavesPerWg - 1) / kWavesPerWg);
-    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_pass<S, 0>), dim3(grid), dim3(kWgThreads), 0, stream, a);
-    else hipLaunchKernelGGL((k_scale_pass<S, 1>), dim3(grid), dim3(kWgThreads), 0, stream, a);
+    const unsigned grid = (unsigned)((a.nseg + kWavesPerWg - 1) / kWavesPerWg);
+    if (scale_mode == 0)
+        hipLaunchKernelGGL((k_scale_pass<S, 0>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, a);
+    else
+        hipLaunchKernelGGL((k_scale_pass<S, 1>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, a);
     return hipGetLastError();
 }
 
@@ -110,17 +126,17 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream)
 {
-    ScaleArgs a{G, ldg, n, k, d, code, ws};
+    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq};
     switch (code.band) {
-        case 1: return launch_scale_pass_s<1>(a, scale_mode, stream);
-        case 2: return launch_scale_pass_s<2>(a, scale_mode, stream);
-        case 3: return launch_scale_pass_s<3>(a, scale_mode, stream);
-        case 4: return launch_scale_pass_s<4>(a, scale_mode, stream);
-        case 5: return launch_scale_pass_s<5>(a, scale_mode, stream);
-        case 6: return launch_scale_pass_s<6>(a, scale_mode, stream);
-        case 7: return launch_scale_pass_s<7>(a, scale_mode, stream);
-        case 8: return launch_scale_pass_s<8>(a, scale_mode, stream);
-        default: return launch_scale_pass_s<0>(a, scale_mode, stream);
+        case 1: return launch_scale_pass_s<1>(G, code, a, scale_mode, stream);
+        case 2: return launch_scale_pass_s<2>(G, code, a, scale_mode, stream);
+        case 3: return launch_scale_pass_s<3>(G, code, a, scale_mode, stream);
+        case 4: return launch_scale_pass_s<4>(G, code, a, scale_mode, stream);
+        case 5: return launch_scale_pass_s<5>(G, code, a, scale_mode, stream);
+        case 6: return launch_scale_pass_s<6>(G, code, a, scale_mode, stream);
+        case 7: return launch_scale_pass_s<7>(G, code, a, scale_mode, stream);
+        case 8: return launch_scale_pass_s<8>(G, code, a, scale_mode, stream);
+        default: return launch_scale_pass_s<0>(G, code, a, scale_mode, stream);
     }
 }
 
@@ -136,29 +152,31 @@ __device__ __forceinline__ float inv16_of(float scale, int bits)
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, PerWorkerBits bits,
+__global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStreams out,
                                                                Workspace ws, float* scales)
 {
     const int i = blockIdx.x;
     const int tid = threadIdx.x;
-    __shared__ float red[kWgThreads];
+    __shared__ uint32_t red[kWgThreads];
     float scale;
     if (MODE == 1) {
-        float m = 0.f;
-        for (int64_t s = tid; s < ws.nseg; s += kWgThreads) m = fmaxf(m, ws.part_max[s * n + i]);
+        uint32_t m = 0u;
+        const uint32_t* part = ws.part_max + (int64_t)i * ws.nseg;
+        for (int64_t s = tid; s < ws.nseg; s += kWgThreads) m = max(m, part[s]);
         red[tid] = m;
         __syncthreads();
         for (int h = kWgThreads / 2; h > 0; h >>= 1) {
-            if (tid < h) red[tid] = fmaxf(red[tid], red[tid + h]);
+            if (tid < h) red[tid] = max(red[tid], red[tid + h]);
             __syncthreads();
         }
-        scale = red[0];
+        scale = __uint_as_float(red[0]);
     } else {
+        const double* part = ws.part_sq + (int64_t)i * ws.nseg;
         // level 3: 64 segments -> group, in order
         for (int64_t g = tid; g < ws.ngroup; g += kWgThreads) {
             double acc = 0.0;
             const int64_t s1 = (g + 1) * kGroupSegs < ws.nseg ? (g + 1) * kGroupSegs : ws.nseg;
-            for (int64_t s = g * kGroupSegs; s < s1; ++s) acc = acc + ws.part_sq[s * n + i];
+            for (int64_t s = g * kGroupSegs; s < s1; ++s) acc = acc + part[s];
             ws.group_sq[(int64_t)i * ws.ngroup + g] = acc;
         }
         __syncthreads();
@@ -171,25 +189,26 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, PerWorkerB
         }
         __syncthreads();
         // level 5: supergroups in order
-        double total = 0.0;
         if (tid == 0) {
+            double total = 0.0;
             for (int64_t u = 0; u < ws.nsuper; ++u) total = total + ws.super_sq[(int64_t)i * ws.nsuper + u];
-            red[0] = (float)sqrt(total);
+            red[0] = __float_as_uint((float)sqrt(total));
         }
         __syncthreads();
-        scale = red[0];
+        scale = __uint_as_float(red[0]);
     }
     if (tid == 0) {
         scales[i] = scale;
-        ws.inv16[i] = inv16_of(scale, bits.bits[i]);
+        const int b = out.bits[i];
+        ws.wq[i] = WorkerQ{inv16_of(scale, b), (uint32_t)b, out.codes[i]};
     }
 }
 
-hipError_t launch_scale_finalize(int n, int scale_mode, const PerWorkerBits& bits,
+hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
-    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, bits, ws, scales);
-    else hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, bits, ws, scales);
+    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, ws, scales);
+    else hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, ws, scales);
     return hipGetLastError();
 }
 
@@ -197,15 +216,13 @@ hipError_t launch_scale_finalize(int n, int scale_mode, const PerWorkerBits& bit
 // K2  encode + stochastic quantize + bit-pack
 // =======================================================================================
 struct QuantArgs {
-    const float* G;
     int64_t ldg;
     int n, k;
     int64_t d;
-    CodeDev code;
-    const float* inv16;
     uint32_t key0, key1, step_lo, step_hi;
-    QuantStreams out;
 };
+
+typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
 
 constexpr int kStageWords = 8 * 16 + 2;  // 256 codes of up to 16 bits, plus spill of zero bits
 
@@ -238,43 +255,56 @@ __device__ __forceinline__ float grid_pos(float f, float inv)
     return fabsf(f) * inv;
 }
 
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wave execute in issue order; this only pins the compiler's order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 struct EpiQuant {
-    const QuantArgs& a;
+    const WorkerQ* __restrict__ wq;
+    uint32_t key0, key1, step_lo, step_hi;
     uint32_t* stage;     // this wave's LDS staging words, all zero between workers
     int lane;
     int64_t block;       // index of this wave's 256-coordinate block
+    int groups_valid;    // 128-code groups of this block that exist in the streams (1 or 2)
     uint32_t ctr0;       // m >> 2 of this lane's coordinates
     int nvalid;
-    bool wave_has_pad;   // wave-uniform: some lane has coordinates >= d
+    bool wave_ragged;    // wave-uniform: some lane has coordinates >= d
     uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
 
-    template <bool ONEBIT>
+    // four rounding decisions; only the grid position differs between the regular grid
+    // (b >= 2) and the two-point grid of a one-bit worker
     __device__ __forceinline__ void codes4(int i, const float4& f, float inv, int b, uint32_t wa,
                                            uint32_t wb, uint32_t (&c)[4])
     {
-        const uint32_t L = ONEBIT ? 1u : ((1u << (b - 1)) - 1u);
         const float fv[4] = {f.x, f.y, f.z, f.w};
         const uint32_t u[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
+        const uint32_t L = b >= 2 ? ((1u << (b - 1)) - 1u) : 1u;
+        const uint32_t signbit = b >= 2 ? (1u << (b - 1)) : 0u;
         bool tie[4];
         float T[4];
+        if (b >= 2) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            T[q] = grid_pos<ONEBIT>(fv[q], inv);
-            c[q] = round_primary(T[q], u[q], L, tie[q]);
+            for (int q = 0; q < 4; ++q) T[q] = grid_pos<false>(fv[q], inv);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) T[q] = grid_pos<true>(fv[q], inv);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] = round_primary(T[q], u[q], L, tie[q]);
         if (__any(tie[0] | tie[1] | tie[2] | tie[3])) {  // about one wave pass in 250
             uint32_t r2[4];
-            philox4x32_10(ctr0, 0x80000000u | (uint32_t)i, a.step_lo, a.step_hi, a.key0, a.key1, r2);
+            philox4x32_10(ctr0, 0x80000000u | (uint32_t)i, step_lo, step_hi, key0, key1, r2);
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 if (tie[q]) c[q] = round_tied(T[q], r2[q], L);
         }
-        if (!ONEBIT) {
-            const uint32_t signbit = 1u << (b - 1);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) c[q] |= (__float_as_uint(fv[q]) >> (32 - b)) & signbit;
-        }
-        if (wave_has_pad) {  // codes of coordinates >= d are zero padding
+        for (int q = 0; q < 4; ++q) c[q] |= (__float_as_uint(fv[q]) >> ((32 - b) & 31)) & signbit;
+        if (wave_ragged) {  // codes of coordinates >= d are zero padding
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 if (q >= nvalid) c[q] = 0u;
@@ -287,7 +317,7 @@ struct EpiQuant {
         uint32_t wa, wb;
         if (EVEN) {
             uint32_t o[4];
-            philox4x32_10(ctr0, (uint32_t)i >> 1, a.step_lo, a.step_hi, a.key0, a.key1, o);
+            philox4x32_10(ctr0, (uint32_t)i >> 1, step_lo, step_hi, key0, key1, o);
             wa = o[0];
             wb = o[1];
             keep2 = o[2];
@@ -296,50 +326,55 @@ struct EpiQuant {
             wa = keep2;
             wb = keep3;
         }
-        const int b = a.out.bits[i];
-        const float inv = a.inv16[i];
+        const WorkerQ q = wq[i];  // wave-uniform: one scalar 16-byte load
+        const int b = (int)q.bits;
         uint32_t c[4];
-        if (b >= 2) codes4<false>(i, f, inv, b, wa, wb, c);
-        else codes4<true>(i, f, inv, b, wa, wb, c);
+        codes4(i, f, q.inv16, b, wa, wb, c);
 
         // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
         const uint32_t bitpos = (uint32_t)lane * 4u * (uint32_t)b;
-        const uint32_t word = bitpos >> 5, sh = bitpos & 31u;
+        uint32_t* slot = stage + (bitpos >> 5);
+        const uint32_t sh = bitpos & 31u;
         if (b <= 8) {
             const uint32_t chunk = c[0] | (c[1] << b) | (c[2] << (2 * b)) | (c[3] << (3 * b));
             const uint64_t v = (uint64_t)chunk << sh;
-            atomicOr(&stage[word], (uint32_t)v);
-            atomicOr(&stage[word + 1], (uint32_t)(v >> 32));
+            atomicOr(slot, (uint32_t)v);
+            atomicOr(slot + 1, (uint32_t)(v >> 32));
         } else {
             const uint64_t chunk = (uint64_t)c[0] | ((uint64_t)c[1] << b) | ((uint64_t)c[2] << (2 * b)) |
                                    ((uint64_t)c[3] << (3 * b));
             const uint64_t v = chunk << sh;
             const uint32_t top = sh ? (uint32_t)(chunk >> (64 - sh)) : 0u;
-            atomicOr(&stage[word], (uint32_t)v);
-            atomicOr(&stage[word + 1], (uint32_t)(v >> 32));
-            atomicOr(&stage[word + 2], top);
+            atomicOr(slot, (uint32_t)v);
+            atomicOr(slot + 1, (uint32_t)(v >> 32));
+            atomicOr(slot + 2, top);
         }
-        // LDS operations of one wave execute in issue order; the fences only stop the compiler
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wave_lds_fence();
+        // the block's 8b words leave as one contiguous, coalesced store; the staging words
+        // are handed back zeroed
         const int nwords = 8 * b;
-        const int64_t total_words = ((a.d + 127) / 128) * 4 * b;
-        uint32_t* dst = reinterpret_cast<uint32_t*>(a.out.codes[i]);
-        for (int w = lane; w < nwords; w += kWave) {
-            const uint32_t v = stage[w];
-            stage[w] = 0u;
-            const int64_t gi = block * nwords + w;
-            if (gi < total_words) dst[gi] = v;
+        const int nstore = 4 * b * groups_valid;
+        global_u32* dst = (global_u32*)q.codes + block * nwords;
+        {
+            const uint32_t v = stage[lane];
+            if (lane < nwords) stage[lane] = 0u;
+            if (lane < nstore) dst[lane] = v;
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (b > 8) {
+            const uint32_t v = stage[lane + kWave];
+            if (lane + kWave < nwords) stage[lane + kWave] = 0u;
+            if (lane + kWave < nstore) dst[lane + kWave] = v;
+        }
+        wave_lds_fence();
     }
 };
 
 template <int S>
-__global__ __launch_bounds__(kWgThreads) void k_quantize(QuantArgs a)
+__global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
+                                                         const int* __restrict__ row_ptr,
+                                                         const int* __restrict__ col,
+                                                         const float* __restrict__ val,
+                                                         const WorkerQ* __restrict__ wq, QuantArgs a)
 {
     __shared__ uint32_t lds_stage[kWavesPerWg][kStageWords];
     const int wave = threadIdx.x / kWave;
@@ -347,42 +382,43 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(QuantArgs a)
     const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
     const int64_t base = block * (int64_t)kBlockCoords;
     for (int w = lane; w < kStageWords; w += kWave) lds_stage[wave][w] = 0u;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_lds_fence();
     if (base >= a.d) return;
     const LaneCoords lc = lane_coords(base + 4 * lane, a.d);
-    EpiQuant epi{a, lds_stage[wave], lane, block, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
-                 __any(lc.nvalid < 4) != 0, 0u, 0u};
-    if constexpr (S > 0) encode_ring<S>(a.G, a.ldg, a.k, a.code.val, lc, epi);
-    else encode_gather(a.G, a.ldg, a.n, CsrView{a.code.row_ptr, a.code.col, a.code.val}, lc, epi);
+    const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
+    EpiQuant epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
+                 groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
+                 lc.wave_ragged, 0u, 0u};
+    if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
+    else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
 }
 
 template <int S>
-static hipError_t launch_quantize_s(const QuantArgs& a, hipStream_t stream)
+static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const WorkerQ* wq,
+                                    const QuantArgs& a, hipStream_t stream)
 {
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
-    hipLaunchKernelGGL((k_quantize<S>), dim3(grid), dim3(kWgThreads), 0, stream, a);
+    hipLaunchKernelGGL((k_quantize<S>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr, code.col,
+                       code.val, wq, a);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           const QuantStreams& out, hipStream_t stream)
+                           hipStream_t stream)
 {
-    QuantArgs a{G, ldg, n, k, d, code, ws.inv16, (uint32_t)seed, (uint32_t)(seed >> 32),
-                (uint32_t)step, (uint32_t)(step >> 32), out};
+    QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
     switch (code.band) {
-        case 1: return launch_quantize_s<1>(a, stream);
-        case 2: return launch_quantize_s<2>(a, stream);
-        case 3: return launch_quantize_s<3>(a, stream);
-        case 4: return launch_quantize_s<4>(a, stream);
-        case 5: return launch_quantize_s<5>(a, stream);
-        case 6: return launch_quantize_s<6>(a, stream);
-        case 7: return launch_quantize_s<7>(a, stream);
-        case 8: return launch_quantize_s<8>(a, stream);
-        default: return launch_quantize_s<0>(a, stream);
+        case 1: return launch_quantize_s<1>(G, code, ws.wq, a, stream);
+        case 2: return launch_quantize_s<2>(G, code, ws.wq, a, stream);
+        case 3: return launch_quantize_s<3>(G, code, ws.wq, a, stream);
+        case 4: return launch_quantize_s<4>(G, code, ws.wq, a, stream);
+        case 5: return launch_quantize_s<5>(G, code, ws.wq, a, stream);
+        case 6: return launch_quantize_s<6>(G, code, ws.wq, a, stream);
+        case 7: return launch_quantize_s<7>(G, code, ws.wq, a, stream);
+        case 8: return launch_quantize_s<8>(G, code, ws.wq, a, stream);
+        default: return launch_quantize_s<0>(G, code, ws.wq, a, stream);
     }
 }
 
@@ -394,16 +430,22 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
 // compile-time constant.
 constexpr int kDecCoords = 32;
 
-struct DecodeArgs {
-    int n;
-    int64_t d;
-    const float* scales;
-    float* ghat;
-    DecodeStreams in;
-};
+// prologue: one entry per ARRIVED worker, in ascending worker order
+__global__ __launch_bounds__(kWgThreads) void k_decode_table(int n, DecodeStreams in,
+                                                             const float* scales, WorkerD* wd)
+{
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    const uint32_t slot = in.slot[i];
+    if (slot == 0xFFFFu) return;
+    const int b = in.bits[i];
+    // weight of one grid unit of worker i: w_i * scale_i / L_i, binary64 then one rounding
+    const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+    wd[slot] = WorkerD{in.codes[i], (float)(((double)in.w[i] * (double)scales[i]) / L), (uint32_t)b};
+}
 
 template <int B>
-__device__ __forceinline__ void decode_words(const uint32_t* __restrict__ src, float coef,
+__device__ __forceinline__ void decode_words(const global_u32* __restrict__ src, float coef,
                                              float (&acc)[kDecCoords])
 {
     uint32_t w[B];
@@ -413,58 +455,60 @@ __device__ __forceinline__ void decode_words(const uint32_t* __restrict__ src, f
     for (int q = 0; q < kDecCoords; ++q) {
         const int bit = q * B;
         const int wi = bit >> 5, sh = bit & 31;
-        uint32_t code = w[wi] >> sh;
-        if (sh + B > 32) code |= w[wi + 1] << (32 - sh);
         float v;
         if (B == 1) {
-            v = (code & 1u) ? 1.0f : -1.0f;
+            v = ((w[wi] >> sh) & 1u) ? 1.0f : -1.0f;
         } else {
-            const uint32_t level = code & ((1u << (B - 1)) - 1u);
-            const uint32_t sign = (code << (32 - B)) & 0x80000000u;
+            // the code's low B-1 bits are the level, its top bit the sign
+            uint32_t x = w[wi];
+            int s = sh;
+            if (sh + B > 32) {  // the code straddles two words: bring it down to bit 0
+                x = __builtin_amdgcn_alignbit(w[(wi + 1) < B ? (wi + 1) : wi], w[wi], sh);
+                s = 0;
+            }
+            const uint32_t level = (x >> s) & ((1u << (B - 1)) - 1u);
+            const uint32_t sign = (x << (32 - B - s)) & 0x80000000u;
             v = __uint_as_float(__float_as_uint((float)level) | sign);
         }
         acc[q] = fmaf(coef, v, acc[q]);
     }
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_decode(DecodeArgs a)
+struct DecodeArgs {
+    int n_arrived;
+    int64_t d;
+    float* ghat;
+};
+
+__global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict__ wd, DecodeArgs a)
 {
-    __shared__ float lds_coef[kMaxWorkers];
-    // weight of one grid unit of worker i: w_i * scale_i / L_i, binary64 then one rounding
-    for (int i = threadIdx.x; i < a.n; i += kWgThreads) {
-        const int b = a.in.bits[i];
-        const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
-        lds_coef[i] = (float)(((double)a.in.w[i] * (double)a.scales[i]) / L);
-    }
-    __syncthreads();
     const int64_t t = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
     const int64_t m0 = t * kDecCoords;
     if (m0 >= a.d) return;
     float acc[kDecCoords];
 #pragma unroll
     for (int q = 0; q < kDecCoords; ++q) acc[q] = 0.f;
-    for (int i = 0; i < a.n; ++i) {
-        if (!a.in.mask[i]) continue;
-        const int b = a.in.bits[i];
-        const float coef = lds_coef[i];
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(a.in.codes[i]) + t * b;
+    for (int e = 0; e < a.n_arrived; ++e) {
+        const WorkerD wk = wd[e];  // wave-uniform: one scalar 16-byte load
+        const int b = (int)wk.bits;
+        const global_u32* src = (const global_u32*)wk.codes + t * b;
         switch (b) {
-            case 1: decode_words<1>(src, coef, acc); break;
-            case 2: decode_words<2>(src, coef, acc); break;
-            case 3: decode_words<3>(src, coef, acc); break;
-            case 4: decode_words<4>(src, coef, acc); break;
-            case 5: decode_words<5>(src, coef, acc); break;
-            case 6: decode_words<6>(src, coef, acc); break;
-            case 7: decode_words<7>(src, coef, acc); break;
-            case 8: decode_words<8>(src, coef, acc); break;
-            case 9: decode_words<9>(src, coef, acc); break;
-            case 10: decode_words<10>(src, coef, acc); break;
-            case 11: decode_words<11>(src, coef, acc); break;
-            case 12: decode_words<12>(src, coef, acc); break;
-            case 13: decode_words<13>(src, coef, acc); break;
-            case 14: decode_words<14>(src, coef, acc); break;
-            case 15: decode_words<15>(src, coef, acc); break;
-            default: decode_words<16>(src, coef, acc); break;
+            case 1: decode_words<1>(src, wk.coef, acc); break;
+            case 2: decode_words<2>(src, wk.coef, acc); break;
+            case 3: decode_words<3>(src, wk.coef, acc); break;
+            case 4: decode_words<4>(src, wk.coef, acc); break;
+            case 5: decode_words<5>(src, wk.coef, acc); break;
+            case 6: decode_words<6>(src, wk.coef, acc); break;
+            case 7: decode_words<7>(src, wk.coef, acc); break;
+            case 8: decode_words<8>(src, wk.coef, acc); break;
+            case 9: decode_words<9>(src, wk.coef, acc); break;
+            case 10: decode_words<10>(src, wk.coef, acc); break;
+            case 11: decode_words<11>(src, wk.coef, acc); break;
+            case 12: decode_words<12>(src, wk.coef, acc); break;
+            case 13: decode_words<13>(src, wk.coef, acc); break;
+            case 14: decode_words<14>(src, wk.coef, acc); break;
+            case 15: decode_words<15>(src, wk.coef, acc); break;
+            default: decode_words<16>(src, wk.coef, acc); break;
         }
     }
     float* dst = a.ghat + m0;
@@ -479,13 +523,16 @@ __global__ __launch_bounds__(kWgThreads) void k_decode(DecodeArgs a)
     }
 }
 
-hipError_t launch_decode(int n, int64_t d, const DecodeStreams& in, const float* scales,
-                         float* ghat, hipStream_t stream)
+hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
+                         const float* scales, const Workspace& ws, float* ghat, hipStream_t stream)
 {
-    DecodeArgs a{n, d, scales, ghat, in};
+    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, ws.wd);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    DecodeArgs a{n_arrived, d, ghat};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    hipLaunchKernelGGL(k_decode, dim3(grid), dim3(kWgThreads), 0, stream, a);
+    hipLaunchKernelGGL(k_decode, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, a);
     return hipGetLastError();
 }
 
