@@ -27,8 +27,15 @@ constexpr int kMaxBand = 8;     // largest replication factor served by the regi
 // Philox4x32 with ten rounds (Salmon et al., SC'11).  Round: the two 32x32->64 products of
 // counter words 0 and 2 with fixed odd multipliers; high halves are mixed with words 1 and 3
 // and the round key; the key advances by Weyl constants.  On gfx950 the wide product is one
-// full-rate v_mad_u64_u32, so a block costs about 60 vector instructions.
+// full-rate v_mad_u64_u32 and the two mixes are one three-input xor each, so a block costs
+// about 40 vector instructions.
 // ---------------------------------------------------------------------------------------
+// a ^ b ^ c in one instruction (gfx950's three-input bitwise op; truth table 0x96 = parity)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return (uint32_t)__builtin_amdgcn_bitop3_b32((int)a, (int)b, (int)c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])
 {
@@ -36,8 +43,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int r = 0; r < 10; ++r) {
         const uint64_t pa = (uint64_t)0xD2511F53u * c0;
         const uint64_t pb = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(pb >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(pa >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(pb >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(pa >> 32), c3, k1);
         c1 = (uint32_t)pb;
         c3 = (uint32_t)pa;
         c0 = n0;
@@ -117,26 +124,29 @@ __device__ __forceinline__ double wave_butterfly_add(double v)
 // loads of one lane's float4
 // ---------------------------------------------------------------------------------------
 struct LaneCoords {
-    int64_t m_load;    // first coordinate the lane loads from (clamped into the row for lanes past d)
+    int lane4;         // which float4 of the block the lane loads (clamped into the vector for lanes past d)
     int nvalid;        // how many of the lane's four coordinates are < d (0..4)
     bool wave_ragged;  // wave-uniform: some lane of this wave has nvalid < 4
 };
 
-__device__ __forceinline__ LaneCoords lane_coords(int64_t m0, int64_t d)
+// base: first coordinate of the wave's block (wave-uniform, < d)
+__device__ __forceinline__ LaneCoords lane_coords(int64_t base, int lane, int64_t d)
 {
     LaneCoords lc;
-    const int64_t left = d - m0;
+    const int64_t left = d - base - 4 * lane;
     lc.nvalid = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
-    lc.m_load = left > 0 ? m0 : ((d - 1) & ~(int64_t)3);
+    const int64_t last4 = (d - 1 - base) >> 2;  // last float4 of the block that holds a coordinate < d
+    lc.lane4 = last4 < lane ? (int)last4 : lane;
     lc.wave_ragged = __any(lc.nvalid < 4) != 0;
     return lc;
 }
 
-// every lane loads (lanes past d re-read the last float4 of the row and are zeroed), so the
-// load needs no per-lane predicate; coordinates >= d count as 0
+// `row` points at the block's first coordinate inside one row of G and is wave-uniform, so
+// the load is a scalar base plus a 32-bit lane offset.  Every lane loads (lanes past d re-read
+// the last float4 and are zeroed), so there is no per-lane predicate; coordinates >= d count 0.
 __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const LaneCoords& lc)
 {
-    float4 v = *reinterpret_cast<const float4*>(row + lc.m_load);
+    float4 v = reinterpret_cast<const float4*>(row)[lc.lane4];
     if (lc.wave_ragged) {
         if (lc.nvalid < 1) v.x = 0.f;
         if (lc.nvalid < 2) v.y = 0.f;
@@ -204,20 +214,20 @@ __device__ __forceinline__ void stash_fill(float4 (&stash)[RingShape<S>::NSTASH]
 template <int S, int r, bool STEADY, class Epi>
 __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
                                           float4 (&stash)[RingShape<S>::NSTASH],
-                                          const float*& next_row, const float* last_row,
-                                          int64_t ldg, int k, const float* __restrict__ bval,
-                                          const LaneCoords& lc, int j0, Epi& epi)
+                                          const float*& next_row, int64_t ldg, int k,
+                                          const float* __restrict__ bval, const LaneCoords& lc,
+                                          int j0, Epi& epi)
 {
     constexpr int P = RingShape<S>::P;
     constexpr int R = RingShape<S>::R;
     const int j = j0 + r;
     if (STEADY) {
-        ring[(r + P) % R] = load_row4(next_row < last_row ? next_row : last_row, lc);
-        next_row += ldg;
+        ring[(r + P) % R] = load_row4(next_row, lc);
+        next_row += (j + P + 1 < k) ? ldg : 0;  // stays on the last row once it is reached
     } else {
         if (j + P < k) {  // prefetch the row that arrives P steps from now
             ring[(r + P) % R] = load_row4(next_row, lc);
-            next_row += ldg;
+            next_row += (j + P + 1 < k) ? ldg : 0;
         }
         if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
             ring[r] = stash_pick<S>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
@@ -237,12 +247,11 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
 template <int S, bool STEADY, class Epi, int... Rs>
 __device__ __forceinline__ void ring_round(float4 (&ring)[RingShape<S>::R],
                                            float4 (&stash)[RingShape<S>::NSTASH],
-                                           const float*& next_row, const float* last_row,
-                                           int64_t ldg, int k, const float* __restrict__ bval,
-                                           const LaneCoords& lc, int j0, Epi& epi,
-                                           std::integer_sequence<int, Rs...>)
+                                           const float*& next_row, int64_t ldg, int k,
+                                           const float* __restrict__ bval, const LaneCoords& lc,
+                                           int j0, Epi& epi, std::integer_sequence<int, Rs...>)
 {
-    (ring_step<S, Rs, STEADY>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi), ...);
+    (ring_step<S, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, epi), ...);
 }
 
 template <int S, class Epi>
@@ -257,8 +266,7 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
     const int steps = k + S - 1;  // row arrivals, the last S-1 being the wrapped rows
     float4 ring[R];
     float4 stash[RingShape<S>::NSTASH];
-    const float* next_row = G;
-    const float* last_row = G + (int64_t)(k - 1) * ldg;
+    const float* next_row = G;  // G already points at the block's first coordinate in row 0
 #pragma unroll
     for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     stash[0] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -266,15 +274,15 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
     for (int r = 0; r < P; ++r) {
         if (r < k) {
             ring[r] = load_row4(next_row, lc);
-            next_row += ldg;
+            next_row += (r + 1 < k) ? ldg : 0;
         }
     }
     int j0 = 0;
-    ring_round<S, false>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
+    ring_round<S, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
     for (j0 = R; j0 + R - 1 < k; j0 += R)
-        ring_round<S, true>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, true>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
     for (; j0 < steps; j0 += R)
-        ring_round<S, false>(ring, stash, next_row, last_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -43,12 +43,12 @@ struct EpiMaxAbs {
     {
         const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
         const uint32_t m = wave_max_nonneg_bits(a);
-        if (lane == 0) atomicMax(&acc[i], m);
+        if (lane == 0) acc[i] = m;
     }
 };
 
-// epilogue for the Euclidean scale: levels 0-2 of the binary64 summation tree (lane value
-// (x0^2+x1^2)+(x2^2+x3^2); exchange-add across the 64 lanes; blocks of a segment in order)
+// epilogue for the Euclidean scale: levels 0 and 1 of the binary64 summation tree (lane value
+// (x0^2+x1^2)+(x2^2+x3^2); exchange-add across the 64 lanes)
 struct EpiSumSq {
     double* acc;  // this wave's LDS slice [n]
     int lane;
@@ -59,10 +59,13 @@ struct EpiSumSq {
         const double s01 = x0 * x0 + x1 * x1;
         const double s23 = x2 * x2 + x3 * x3;
         const double q = wave_butterfly_add(s01 + s23);
-        if (lane == 0) acc[i] = acc[i] + q;
+        if (lane == 0) acc[i] = q;
     }
 };
 
+// One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it; the
+// four block values of every worker meet in LDS and are combined in block order (level 2 of
+// the tree), which keeps the result independent of how the waves were scheduled.
 template <int S, int MODE>
 __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restrict__ G,
                                                            const int* __restrict__ row_ptr,
@@ -71,39 +74,44 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
                                                            ScaleArgs a)
 {
     __shared__ double lds_acc[kWavesPerWg][kMaxWorkers];
-    const int wave = threadIdx.x / kWave;
+    // the wave index is the same for all lanes: tell the compiler, so that everything derived
+    // from it (block base, pointers) lives in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
-    const int64_t seg = (int64_t)blockIdx.x * kWavesPerWg + wave;
+    const int64_t seg = blockIdx.x;
+    const int64_t base = (seg * kSegBlocks + wave) * (int64_t)kBlockCoords;
 
     double* accd = lds_acc[wave];
     uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
-    for (int i = lane; i < a.n; i += kWave) {
-        if (MODE == 0) accd[i] = 0.0;
-        else accu[i] = 0u;
-    }
-    __syncthreads();
-
-    if (seg < a.nseg) {
-        for (int blk = 0; blk < kSegBlocks; ++blk) {
-            const int64_t base = (seg * kSegBlocks + blk) * (int64_t)kBlockCoords;
-            if (base >= a.d) break;
-            const LaneCoords lc = lane_coords(base + 4 * lane, a.d);
-            if (MODE == 0) {
-                EpiSumSq epi{accd, lane};
-                if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
-                else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
-            } else {
-                EpiMaxAbs epi{accu, lane};
-                if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
-                else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
-            }
+    if (base < a.d) {
+        const LaneCoords lc = lane_coords(base, lane, a.d);
+        if (MODE == 0) {
+            EpiSumSq epi{accd, lane};
+            if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
+            else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+        } else {
+            EpiMaxAbs epi{accu, lane};
+            if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
+            else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+        }
+    } else {  // a block past the end of the vector contributes nothing
+        for (int i = lane; i < a.n; i += kWave) {
+            if (MODE == 0) accd[i] = 0.0;
+            else accu[i] = 0u;
         }
     }
     __syncthreads();
-    if (seg < a.nseg) {
-        for (int i = lane; i < a.n; i += kWave) {
-            if (MODE == 0) a.part_sq[(int64_t)i * a.nseg + seg] = accd[i];
-            else a.part_max[(int64_t)i * a.nseg + seg] = accu[i];
+    for (int i = threadIdx.x; i < a.n; i += kWgThreads) {
+        if (MODE == 0) {
+            double sum = 0.0;
+#pragma unroll
+            for (int w = 0; w < kWavesPerWg; ++w) sum = sum + lds_acc[w][i];
+            a.part_sq[(int64_t)i * a.nseg + seg] = sum;
+        } else {
+            uint32_t m = 0u;
+#pragma unroll
+            for (int w = 0; w < kWavesPerWg; ++w) m = max(m, reinterpret_cast<uint32_t*>(lds_acc[w])[i]);
+            a.part_max[(int64_t)i * a.nseg + seg] = m;
         }
     }
 }
@@ -112,7 +120,7 @@ template <int S>
 static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const ScaleArgs& a,
                                       int scale_mode, hipStream_t stream)
 {
-    const unsigned grid = (unsigned)((a.nseg + kWavesPerWg - 1) / kWavesPerWg);
+    const unsigned grid = (unsigned)a.nseg;
     if (scale_mode == 0)
         hipLaunchKernelGGL((k_scale_pass<S, 0>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
                            code.col, code.val, a);
@@ -162,7 +170,16 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     if (MODE == 1) {
         uint32_t m = 0u;
         const uint32_t* part = ws.part_max + (int64_t)i * ws.nseg;
-        for (int64_t s = tid; s < ws.nseg; s += kWgThreads) m = max(m, part[s]);
+        for (int64_t s0 = tid; s0 < ws.nseg; s0 += 8 * kWgThreads) {
+            uint32_t v[8];  // eight independent loads in flight per lane
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t s = s0 + (int64_t)u * kWgThreads;
+                v[u] = s < ws.nseg ? part[s] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m = max(m, v[u]);
+        }
         red[tid] = m;
         __syncthreads();
         for (int h = kWgThreads / 2; h > 0; h >>= 1) {
@@ -176,7 +193,14 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
         for (int64_t g = tid; g < ws.ngroup; g += kWgThreads) {
             double acc = 0.0;
             const int64_t s1 = (g + 1) * kGroupSegs < ws.nseg ? (g + 1) * kGroupSegs : ws.nseg;
-            for (int64_t s = g * kGroupSegs; s < s1; ++s) acc = acc + part[s];
+            for (int64_t s0 = g * kGroupSegs; s0 < s1; s0 += 8) {
+                double v[8];  // loads first, then the additions in segment order
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = s0 + u < s1 ? part[s0 + u] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < s1) acc = acc + v[u];
+            }
             ws.group_sq[(int64_t)i * ws.ngroup + g] = acc;
         }
         __syncthreads();
@@ -332,7 +356,7 @@ struct EpiQuant {
         codes4(i, f, q.inv16, b, wa, wb, c);
 
         // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
-        const uint32_t bitpos = (uint32_t)lane * 4u * (uint32_t)b;
+        const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
         uint32_t* slot = stage + (bitpos >> 5);
         const uint32_t sh = bitpos & 31u;
         if (b <= 8) {
@@ -377,20 +401,20 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
                                                          const WorkerQ* __restrict__ wq, QuantArgs a)
 {
     __shared__ uint32_t lds_stage[kWavesPerWg][kStageWords];
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
     const int lane = threadIdx.x % kWave;
     const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
     const int64_t base = block * (int64_t)kBlockCoords;
     for (int w = lane; w < kStageWords; w += kWave) lds_stage[wave][w] = 0u;
     wave_lds_fence();
     if (base >= a.d) return;
-    const LaneCoords lc = lane_coords(base + 4 * lane, a.d);
+    const LaneCoords lc = lane_coords(base, lane, a.d);
     const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
     EpiQuant epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
                  groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
                  lc.wave_ragged, 0u, 0u};
-    if constexpr (S > 0) encode_ring<S>(G, a.ldg, a.k, val, lc, epi);
-    else encode_gather(G, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+    if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
+    else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
 }
 
 template <int S>
