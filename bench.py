@@ -42,6 +42,21 @@ def build_problem(cfg, api, code_kind):
     return p, bits, (row_ptr, col, val), w
 
 
+def stored_traffic(tag, kernel):
+    """HBM bytes per launch of `kernel` as measured offline with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (scaled by the calibration copy) and recorded in profiles/traffic_<tag>.txt;
+    None when no such record exists.  bench.py itself never runs the profiler."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{tag}.txt")
+    if not os.path.exists(path):
+        return None, None
+    with open(path) as fh:
+        for line in fh:
+            f = line.split()
+            if len(f) >= 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
+                return float(f[2]), os.path.relpath(path, ROOT)
+    return None, None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,7 +66,10 @@ def main():
     ap.add_argument("--scale", default="maxabs", choices=["maxabs", "l2"])
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-log2", type=int, default=21)
+    ap.add_argument("--cpu-sample-log2", type=int, default=23,
+                    help="the oracle is timed on the first 2^this coordinates (all partitions)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain 1 GiB copy kernel (reference for the traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (the design for "
@@ -78,6 +96,12 @@ def main():
     masks = [I.arrival_mask(cfg, p, t) for t in range(W + K)]     # sampled outside the timed region
     seed = cfg.philox_seed
 
+    if args.calibrate:   # known traffic: reads 2^30 bytes, writes 2^30 bytes
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        api.agc_calibration_copy(dst, src, 1 << 30)
+        torch.cuda.synchronize()
+        del src, dst
     for t in range(W):
         ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
     torch.cuda.synchronize()
@@ -113,9 +137,11 @@ def main():
     dom_avg_s = kernels[dominant]["avg_ms"] * 1e-3
     achieved = alg_bytes[dominant] / dom_avg_s / 1e9
     step_alg_bytes = sum(alg_bytes.values())
+    traffic, traffic_src = stored_traffic(f"{cfg.name}_{args.code}_{args.scale}", dominant)
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "traffic_source": traffic_src,
         "avg_launch_ms": kernels[dominant]["avg_ms"],
         "alg_bytes_per_launch": alg_bytes[dominant],
         "step_alg_bytes": step_alg_bytes,
@@ -146,8 +172,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} workers, k={k} partitions, s={cfg.s}, d={d}, "
                                f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
                                f"{args.code} code, {args.scale} scale",
-                   "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
                    "code_path": ctx.agc_code_path()},
+        "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels": kernels,

@@ -74,7 +74,8 @@ typedef struct {
  * Context
  * ------------------------------------------------------------------------------------ */
 /* Creates a context for n workers, k partitions, d coordinates on the current device and
- * allocates its workspace (per-segment scale partials: about 8*n*ceil(d/4096) bytes).
+ * allocates its workspace (per-segment scale partials, 4 or 8 bytes * n * ceil(d/1024), and
+ * two n-entry tables).
  * opts may be NULL (AGC_SCALE_MAXABS, no 1-bit).  Limits: 1 <= n <= AGC_MAX_WORKERS,
  * 1 <= k <= 65536, 1 <= d <= 2^33. */
 agc_status agc_create(agc_ctx **out, int n_workers, int k_parts, int64_t d, const agc_opts *opts);
@@ -121,8 +122,9 @@ const char *agc_last_error(const agc_ctx *ctx);
  *
  * AGC_SCALE_L2 tree (binary64): 256-coordinate blocks; slot l of a block owns coordinates
  * 4l..4l+3 and holds (x0^2+x1^2)+(x2^2+x3^2); exchange-add over slots at distances
- * 1,2,4,8,16,32; 16 blocks are summed in order into a segment, 64 segments in order into a
- * group, groups in order into S.
+ * 1,2,4,8,16,32; 4 blocks are summed in order into a segment, 64 segments in order into a
+ * group, 64 groups in order into a supergroup, supergroups in order into S (every
+ * sequential sum starts from 0.0).
  *
  *   G_dev      device, k x d binary32, row-major with row stride ldg elements (ldg >= d,
  *              ldg % 4 == 0, base 16-byte aligned); read-only
@@ -166,6 +168,11 @@ agc_status agc_profile_enable(agc_ctx *ctx, int on);
  * launches[j] for each kernel index j since the previous read. */
 agc_status agc_profile_read(agc_ctx *ctx, double total_ms[AGC_NUM_KERNELS],
                             int64_t launches[AGC_NUM_KERNELS]);
+
+/* Measurement utility, not part of the method: a plain copy kernel that reads `bytes` and
+ * writes `bytes` (device pointers, 16-byte aligned, bytes a multiple of 16).  Profiling runs
+ * use it as the kernel of known size against which the memory-traffic counters are scaled. */
+agc_status agc_calibration_copy(void *dst_dev, const void *src_dev, int64_t bytes, void *hip_stream);
 
 /* --------------------------------------------------------------------------------------
  * Host-side design routines (no GPU work; run once per change of the system statistics)

@@ -316,6 +316,12 @@ uint32_t agc_oracle_unpack_one(const uint8_t *stream, int bits, int64_t m)
     return code;
 }
 
+void agc_oracle_unpack_range(const uint8_t *stream, int bits, int64_t m0, int64_t m1,
+                             uint32_t *codes)
+{
+    for (int64_t m = m0; m < m1; ++m) codes[m - m0] = agc_oracle_unpack_one(stream, bits, m);
+}
+
 void agc_oracle_unpack(const uint8_t *stream, int64_t d, int bits, uint32_t *codes)
 {
     for (int64_t m = 0; m < d; ++m) codes[m] = agc_oracle_unpack_one(stream, bits, m);

@@ -52,6 +52,8 @@ def lib():
         L.agc_oracle_pack.restype = None
         L.agc_oracle_unpack.argtypes = [_u8p, C.c_int64, C.c_int, _u32p]
         L.agc_oracle_unpack.restype = None
+        L.agc_oracle_unpack_range.argtypes = [_u8p, C.c_int, C.c_int64, C.c_int64, _u32p]
+        L.agc_oracle_unpack_range.restype = None
         L.agc_oracle_code_value.argtypes = [C.c_uint32, C.c_int]
         L.agc_oracle_code_value.restype = C.c_float
         L.agc_oracle_coef.argtypes = [C.c_float, C.c_float, C.c_int]
@@ -224,6 +226,13 @@ def unpack(stream, d, bits):
     stream, sp = _u8(stream)
     out = np.zeros(d, dtype=np.uint32)
     lib().agc_oracle_unpack(sp, int(d), int(bits), out.ctypes.data_as(_u32p))
+    return out
+
+
+def unpack_range(stream, bits, m0, m1):
+    stream, sp = _u8(stream)
+    out = np.zeros(m1 - m0, dtype=np.uint32)
+    lib().agc_oracle_unpack_range(sp, int(bits), int(m0), int(m1), out.ctypes.data_as(_u32p))
     return out
 
 

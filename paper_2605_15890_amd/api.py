@@ -21,6 +21,7 @@ KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
+    "agc_calibration_copy",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
 ]
@@ -79,6 +80,8 @@ def load():
     L.agc_step.argtypes = [_vp, _vp, C.c_int64, _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64,
                            C.POINTER(_vp), _vp, _vp, _vp]
     L.agc_step.restype = C.c_int
+    L.agc_calibration_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
+    L.agc_calibration_copy.restype = C.c_int
     L.agc_profile_enable.argtypes = [_vp, C.c_int]
     L.agc_profile_enable.restype = C.c_int
     L.agc_profile_read.argtypes = [_vp, _f64p, C.POINTER(C.c_int64)]
@@ -283,6 +286,14 @@ class Context:
         cnt = (C.c_int64 * AGC_NUM_KERNELS)()
         self._check(self.lib.agc_profile_read(self.h, ms, cnt))
         return {KERNEL_NAMES[j]: (float(ms[j]), int(cnt[j])) for j in range(AGC_NUM_KERNELS)}
+
+
+def agc_calibration_copy(dst, src, nbytes, stream=None):
+    """Plain copy of nbytes between two torch tensors (counter calibration)."""
+    st = load().agc_calibration_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), int(nbytes),
+                                     _stream_handle(stream))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_calibration_copy")
 
 
 def padded_rows(k, d, device="cuda"):

@@ -357,6 +357,16 @@ agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits
     return agc_decode(c, codes, scales, bits, w, mask, ghat, hip_stream);
 }
 
+agc_status agc_calibration_copy(void* dst_dev, const void* src_dev, int64_t bytes, void* hip_stream)
+{
+    if (!dst_dev || !src_dev || bytes <= 0) return AGC_EINVAL;
+    if ((bytes & 15) || (reinterpret_cast<uintptr_t>(dst_dev) & 15u) || (reinterpret_cast<uintptr_t>(src_dev) & 15u))
+        return AGC_EALIGN;
+    if (bytes / 16 / 256 >= ((int64_t)1 << 31)) return AGC_ESHAPE;
+    hipError_t e = agc::launch_calibration_copy(dst_dev, src_dev, bytes, reinterpret_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? AGC_OK : AGC_EHIP;
+}
+
 agc_status agc_profile_enable(agc_ctx* c, int on)
 {
     if (!c) return AGC_EINVAL;

@@ -174,12 +174,18 @@ __device__ __forceinline__ float4 fma4(float a, const float4& g, const float4& c
 // compile time (the quantizer shares one Philox block between workers 2q and 2q+1).  The
 // epilogue is called for workers 0..n-1 in ascending order.
 // ---------------------------------------------------------------------------------------
-template <int S>
-struct RingShape {
-    static constexpr int P = ((S + 4) & 1) ? 5 : 4;
+// PF = requested prefetch distance in rows (made one larger when S + PF would be odd)
+template <int S, int PF>
+struct RingShapeT {
+    static constexpr int P = ((S + PF) & 1) ? PF + 1 : PF;
     static constexpr int R = S + P;
     static constexpr int NSTASH = S > 1 ? S - 1 : 1;
 };
+#ifndef AGC_PREFETCH_ROWS
+#define AGC_PREFETCH_ROWS 4
+#endif
+template <int S>
+using RingShape = RingShapeT<S, AGC_PREFETCH_ROWS>;
 
 // value select (the operands are read before the choice, so the choice is between registers)
 __device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)

@@ -69,4 +69,7 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
 hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
                          const float* scales, const Workspace& ws, float* ghat, hipStream_t stream);
 
+// plain streaming copy of `bytes` (multiple of 16) bytes, used to calibrate hardware counters
+hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
+
 }  // namespace agc

@@ -393,8 +393,13 @@ struct EpiQuant {
     }
 };
 
+#ifdef AGC_K2_WAVES
+#define AGC_K2_ATTR __attribute__((amdgpu_waves_per_eu(AGC_K2_WAVES, AGC_K2_WAVES)))
+#else
+#define AGC_K2_ATTR
+#endif
 template <int S>
-__global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
+__global__ __launch_bounds__(kWgThreads) AGC_K2_ATTR void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,
@@ -557,6 +562,25 @@ hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& i
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
     hipLaunchKernelGGL(k_decode, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, a);
+    return hipGetLastError();
+}
+
+// =======================================================================================
+// counter calibration: a copy that moves exactly `bytes` in and `bytes` out
+// =======================================================================================
+__global__ __launch_bounds__(kWgThreads) void k_calibration_copy(const float4* __restrict__ src,
+                                                                 float4* __restrict__ dst, int64_t n16)
+{
+    const int64_t i = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream)
+{
+    const int64_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)((n16 + kWgThreads - 1) / kWgThreads);
+    hipLaunchKernelGGL(k_calibration_copy, dim3(grid), dim3(kWgThreads), 0, stream,
+                       static_cast<const float4*>(src), static_cast<float4*>(dst), n16);
     return hipGetLastError();
 }
 
