@@ -143,11 +143,13 @@ __device__ __forceinline__ LaneCoords lane_coords(int64_t base, int lane, int64_
 
 // `row` points at the block's first coordinate inside one row of G and is wave-uniform, so
 // the load is a scalar base plus a 32-bit lane offset.  Every lane loads (lanes past d re-read
-// the last float4 and are zeroed), so there is no per-lane predicate; coordinates >= d count 0.
+// the last float4), so there is no per-lane predicate; with RAGGED the coordinates >= d are
+// zeroed, without it the caller guarantees that the whole block lies inside the vector.
+template <bool RAGGED>
 __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const LaneCoords& lc)
 {
     float4 v = reinterpret_cast<const float4*>(row)[lc.lane4];
-    if (lc.wave_ragged) {
+    if (RAGGED) {
         if (lc.nvalid < 1) v.x = 0.f;
         if (lc.nvalid < 2) v.y = 0.f;
         if (lc.nvalid < 3) v.z = 0.f;
@@ -228,11 +230,11 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
     constexpr int R = RingShape<S>::R;
     const int j = j0 + r;
     if (STEADY) {
-        ring[(r + P) % R] = load_row4(next_row, lc);
+        ring[(r + P) % R] = load_row4<false>(next_row, lc);
         next_row += (j + P + 1 < k) ? ldg : 0;  // stays on the last row once it is reached
     } else {
         if (j + P < k) {  // prefetch the row that arrives P steps from now
-            ring[(r + P) % R] = load_row4(next_row, lc);
+            ring[(r + P) % R] = load_row4<false>(next_row, lc);
             next_row += (j + P + 1 < k) ? ldg : 0;
         }
         if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
@@ -279,7 +281,7 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
 #pragma unroll
     for (int r = 0; r < P; ++r) {
         if (r < k) {
-            ring[r] = load_row4(next_row, lc);
+            ring[r] = load_row4<false>(next_row, lc);
             next_row += (r + 1 < k) ? ldg : 0;
         }
     }
@@ -301,26 +303,43 @@ struct CsrView {
     const float* __restrict__ val;
 };
 
+template <bool RAGGED>
 __device__ __forceinline__ float4 encode_gather_one(const float* __restrict__ G, int64_t ldg,
                                                     const CsrView& B, int i, const LaneCoords& lc)
 {
     const int e0 = B.row_ptr[i], e1 = B.row_ptr[i + 1];
     float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
     if (e0 < e1) {
-        f = mul4(B.val[e0], load_row4(G + (int64_t)B.col[e0] * ldg, lc));
+        f = mul4(B.val[e0], load_row4<RAGGED>(G + (int64_t)B.col[e0] * ldg, lc));
         for (int e = e0 + 1; e < e1; ++e)
-            f = fma4(B.val[e], load_row4(G + (int64_t)B.col[e] * ldg, lc), f);
+            f = fma4(B.val[e], load_row4<RAGGED>(G + (int64_t)B.col[e] * ldg, lc), f);
     }
     return f;
 }
 
-template <class Epi>
+template <bool RAGGED, class Epi>
 __device__ __forceinline__ void encode_gather(const float* __restrict__ G, int64_t ldg, int n,
                                               const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     for (int i = 0; i < n; i += 2) {
-        epi.template worker<true>(i, encode_gather_one(G, ldg, B, i, lc));
-        if (i + 1 < n) epi.template worker<false>(i + 1, encode_gather_one(G, ldg, B, i + 1, lc));
+        epi.template worker<true>(i, encode_gather_one<RAGGED>(G, ldg, B, i, lc));
+        if (i + 1 < n) epi.template worker<false>(i + 1, encode_gather_one<RAGGED>(G, ldg, B, i + 1, lc));
+    }
+}
+
+// One block of 256 coordinates for all workers.  The register ring serves whole blocks of a
+// cyclic-band code; the one block that straddles d (and any other code) goes through the
+// gather driver, which masks the coordinates past the end.  Both give identical bits.
+template <int S, class Epi>
+__device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_t ldg, int n, int k,
+                                             const CsrView& B, const LaneCoords& lc, Epi& epi)
+{
+    if constexpr (S > 0) {
+        if (!lc.wave_ragged) encode_ring<S>(G, ldg, k, B.val, lc, epi);
+        else encode_gather<true>(G, ldg, n, B, lc, epi);
+    } else {
+        if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);
+        else encode_gather<true>(G, ldg, n, B, lc, epi);
     }
 }
 

@@ -87,12 +87,10 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
         const LaneCoords lc = lane_coords(base, lane, a.d);
         if (MODE == 0) {
             EpiSumSq epi{accd, lane};
-            if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
-            else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
         } else {
             EpiMaxAbs epi{accu, lane};
-            if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
-            else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
         }
     } else {  // a block past the end of the vector contributes nothing
         for (int i = lane; i < a.n; i += kWave) {
@@ -306,8 +304,8 @@ struct EpiQuant {
     {
         const float fv[4] = {f.x, f.y, f.z, f.w};
         const uint32_t u[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
-        const uint32_t L = b >= 2 ? ((1u << (b - 1)) - 1u) : 1u;
-        const uint32_t signbit = b >= 2 ? (1u << (b - 1)) : 0u;
+        const uint32_t L = (b >= 2) ? ((1u << (b - 1)) - 1u) : 1u;
+        const uint32_t signbit = (b >= 2) ? (1u << (b - 1)) : 0u;
         bool tie[4];
         float T[4];
         if (b >= 2) {
@@ -393,13 +391,8 @@ struct EpiQuant {
     }
 };
 
-#ifdef AGC_K2_WAVES
-#define AGC_K2_ATTR __attribute__((amdgpu_waves_per_eu(AGC_K2_WAVES, AGC_K2_WAVES)))
-#else
-#define AGC_K2_ATTR
-#endif
 template <int S>
-__global__ __launch_bounds__(kWgThreads) AGC_K2_ATTR void k_quantize(const float* __restrict__ G,
+__global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,
@@ -418,8 +411,7 @@ __global__ __launch_bounds__(kWgThreads) AGC_K2_ATTR void k_quantize(const float
     EpiQuant epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
                  groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
                  lc.wave_ragged, 0u, 0u};
-    if constexpr (S > 0) encode_ring<S>(G + base, a.ldg, a.k, val, lc, epi);
-    else encode_gather(G + base, a.ldg, a.n, CsrView{row_ptr, col, val}, lc, epi);
+    encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
 }
 
 template <int S>
