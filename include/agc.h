@@ -169,6 +169,27 @@ agc_status agc_profile_enable(agc_ctx *ctx, int on);
 agc_status agc_profile_read(agc_ctx *ctx, double total_ms[AGC_NUM_KERNELS],
                             int64_t launches[AGC_NUM_KERNELS]);
 
+/* --------------------------------------------------------------------------------------
+ * End-to-end least-squares loop (the producer of G and the consumer of g_hat)
+ * ------------------------------------------------------------------------------------ */
+/* Partial gradients of the least-squares loss 0.5 * ||X_p beta - y_p||^2 of k equal, contiguous
+ * data partitions (Sec. II-A: g_j = grad L(D_j, beta)):  G[p,:] = X_p^T (X_p beta - y_p).
+ *   X_dev     device, n_rows x n_feat bfloat16 (upper halves of binary32), row-major, 16-byte aligned
+ *   y_dev     device, n_rows floats;  beta_dev  device, n_feat floats
+ *   G_dev     device, k_parts x n_feat floats with row stride ldg; overwritten
+ *   resid_dev device, n_rows floats; receives X beta - y (its squared norm is twice the loss)
+ *   workspace_dev device, agc_ls_workspace_floats(...) floats, 16-byte aligned; scratch
+ * Products are exact (beta enters as an exact three-way bfloat16 split on the matrix cores),
+ * accumulation is binary32 in a fixed order, so the result is reproducible run to run.
+ * Shapes: n_feat a multiple of 128 and <= 8192; n_rows a multiple of 16 * k_parts (AGC_ESHAPE). */
+int64_t agc_ls_workspace_floats(int64_t n_rows, int n_feat, int k_parts);
+agc_status agc_ls_partial_gradients(const void *X_dev, int64_t n_rows, int n_feat, const float *y_dev,
+                                    const float *beta_dev, int k_parts, float *G_dev, int64_t ldg,
+                                    float *resid_dev, float *workspace_dev, void *hip_stream);
+/* Gradient-descent update of Sec. II-A: beta <- beta - lr * g_hat (one fused multiply-add per
+ * coordinate), device pointers, d floats each. */
+agc_status agc_gd_update(float *beta_dev, const float *ghat_dev, float lr, int64_t d, void *hip_stream);
+
 /* Measurement utility, not part of the method: a plain copy kernel that reads `bytes` and
  * writes `bytes` (device pointers, 16-byte aligned, bytes a multiple of 16).  Profiling runs
  * use it as the kernel of known size against which the memory-traffic counters are scaled. */

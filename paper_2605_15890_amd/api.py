@@ -21,7 +21,7 @@ KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
-    "agc_calibration_copy",
+    "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
 ]
@@ -80,6 +80,13 @@ def load():
     L.agc_step.argtypes = [_vp, _vp, C.c_int64, _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64,
                            C.POINTER(_vp), _vp, _vp, _vp]
     L.agc_step.restype = C.c_int
+    L.agc_ls_workspace_floats.argtypes = [C.c_int64, C.c_int, C.c_int]
+    L.agc_ls_workspace_floats.restype = C.c_int64
+    L.agc_ls_partial_gradients.argtypes = [_vp, C.c_int64, C.c_int, _vp, _vp, C.c_int, _vp, C.c_int64, _vp,
+                                           _vp, _vp]
+    L.agc_ls_partial_gradients.restype = C.c_int
+    L.agc_gd_update.argtypes = [_vp, _vp, C.c_float, C.c_int64, _vp]
+    L.agc_gd_update.restype = C.c_int
     L.agc_calibration_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
     L.agc_calibration_copy.restype = C.c_int
     L.agc_profile_enable.argtypes = [_vp, C.c_int]
@@ -286,6 +293,28 @@ class Context:
         cnt = (C.c_int64 * AGC_NUM_KERNELS)()
         self._check(self.lib.agc_profile_read(self.h, ms, cnt))
         return {KERNEL_NAMES[j]: (float(ms[j]), int(cnt[j])) for j in range(AGC_NUM_KERNELS)}
+
+
+def agc_ls_workspace_floats(n_rows, n_feat, k_parts):
+    return int(load().agc_ls_workspace_floats(int(n_rows), int(n_feat), int(k_parts)))
+
+
+def agc_ls_partial_gradients(X, y, beta, k_parts, G, resid, workspace, stream=None, check=True):
+    """X: (n_rows, n_feat) torch.bfloat16 on the GPU; G: (k_parts, n_feat) float32 view."""
+    st = load().agc_ls_partial_gradients(C.c_void_p(X.data_ptr()), X.shape[0], X.shape[1],
+                                         C.c_void_p(y.data_ptr()), C.c_void_p(beta.data_ptr()), int(k_parts),
+                                         C.c_void_p(G.data_ptr()), G.stride(0), C.c_void_p(resid.data_ptr()),
+                                         C.c_void_p(workspace.data_ptr()), _stream_handle(stream))
+    if check and st != AGC_OK:
+        raise AgcError(st, "agc_ls_partial_gradients")
+    return st
+
+
+def agc_gd_update(beta, ghat, lr, stream=None):
+    st = load().agc_gd_update(C.c_void_p(beta.data_ptr()), C.c_void_p(ghat.data_ptr()), float(lr),
+                              beta.numel(), _stream_handle(stream))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_gd_update")
 
 
 def agc_calibration_copy(dst, src, nbytes, stream=None):

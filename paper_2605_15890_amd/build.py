@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagc.so")
-SOURCES = ["agc_kernels.hip", "agc_api.cpp", "agc_host.cpp"]
+SOURCES = ["agc_kernels.hip", "agc_ls_kernels.hip", "agc_api.cpp", "agc_host.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -357,6 +357,35 @@ agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits
     return agc_decode(c, codes, scales, bits, w, mask, ghat, hip_stream);
 }
 
+int64_t agc_ls_workspace_floats(int64_t n_rows, int n_feat, int k_parts)
+{
+    if (n_rows <= 0 || n_feat <= 0 || k_parts <= 0) return 0;
+    return (int64_t)k_parts * agc::ls_wg_per_part(n_rows, k_parts) * n_feat;
+}
+
+agc_status agc_ls_partial_gradients(const void* X_dev, int64_t n_rows, int n_feat, const float* y_dev,
+                                    const float* w_dev, int k_parts, float* G_dev, int64_t ldg,
+                                    float* resid_dev, float* workspace_dev, void* hip_stream)
+{
+    if (!X_dev || !y_dev || !w_dev || !G_dev || !resid_dev || !workspace_dev) return AGC_EINVAL;
+    if (n_rows <= 0 || k_parts <= 0 || n_feat <= 0 || n_feat > 8192 || (n_feat % 128) != 0) return AGC_ESHAPE;
+    if (n_rows % ((int64_t)k_parts * 16) != 0 || ldg < n_feat) return AGC_ESHAPE;
+    if ((reinterpret_cast<uintptr_t>(X_dev) & 15u) || (reinterpret_cast<uintptr_t>(workspace_dev) & 15u) ||
+        (reinterpret_cast<uintptr_t>(G_dev) & 3u))
+        return AGC_EALIGN;
+    hipError_t e = agc::launch_ls_partial_gradients(X_dev, n_rows, n_feat, y_dev, w_dev, k_parts, G_dev, ldg,
+                                                    resid_dev, workspace_dev,
+                                                    reinterpret_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? AGC_OK : AGC_EHIP;
+}
+
+agc_status agc_gd_update(float* beta_dev, const float* ghat_dev, float lr, int64_t d, void* hip_stream)
+{
+    if (!beta_dev || !ghat_dev || d <= 0) return AGC_EINVAL;
+    hipError_t e = agc::launch_gd_update(beta_dev, ghat_dev, lr, d, reinterpret_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? AGC_OK : AGC_EHIP;
+}
+
 agc_status agc_calibration_copy(void* dst_dev, const void* src_dev, int64_t bytes, void* hip_stream)
 {
     if (!dst_dev || !src_dev || bytes <= 0) return AGC_EINVAL;

@@ -137,3 +137,39 @@ def partial_gradients_torch(cfg: Config, device, d: Optional[int] = None, seed_o
             row.div_(torch.sqrt(chi / 3.0)).mul_(cfg.extra["scale"])
             del chi, tmp
     return G
+
+
+# ----------------------------------------------------------------------------------------
+# least-squares problem of the end-to-end loop: X ~ N(0, 1/F) stored as bfloat16,
+# y = X w* + 0.01 * noise (the paper's own experiments train detection models; this synthetic
+# regression only supplies partial gradients that come from an actual loss)
+# ----------------------------------------------------------------------------------------
+def least_squares_numpy(n_rows: int, n_feat: int, seed: int = 5):
+    """Returns (X as uint16 bfloat16 bit patterns, y float32, w_star float32)."""
+    rng = np.random.default_rng(15890 + seed)
+    X = (rng.standard_normal((n_rows, n_feat), dtype=np.float32) / np.float32(np.sqrt(n_feat)))
+    u = X.view(np.uint32).astype(np.uint64)
+    X_bits = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)     # round to nearest even
+    Xb = (X_bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    w_star = rng.standard_normal(n_feat, dtype=np.float32)
+    y = (Xb.astype(np.float64) @ w_star.astype(np.float64)
+         + 0.01 * rng.standard_normal(n_rows)).astype(np.float32)
+    return X_bits, y, w_star
+
+
+def least_squares_torch(n_rows: int, n_feat: int, device, seed: int = 5):
+    """Same law generated on the device, slab by slab (X is 8 GiB at the full configuration).
+    Returns (X torch.bfloat16, y float32, w_star float32)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(15890 + seed)
+    w_star = torch.randn(n_feat, generator=gen, device=device, dtype=torch.float32)
+    X = torch.empty((n_rows, n_feat), dtype=torch.bfloat16, device=device)
+    y = torch.empty(n_rows, dtype=torch.float32, device=device)
+    slab = 1 << 15
+    for r0 in range(0, n_rows, slab):
+        r1 = min(n_rows, r0 + slab)
+        xs = torch.randn((r1 - r0, n_feat), generator=gen, device=device, dtype=torch.float32) / (n_feat ** 0.5)
+        X[r0:r1] = xs.to(torch.bfloat16)
+        y[r0:r1] = X[r0:r1].to(torch.float32) @ w_star + 0.01 * torch.randn(r1 - r0, generator=gen, device=device)
+    return X, y, w_star
