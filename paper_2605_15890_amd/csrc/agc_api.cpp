@@ -360,7 +360,7 @@ agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits
 int64_t agc_ls_workspace_floats(int64_t n_rows, int n_feat, int k_parts)
 {
     if (n_rows <= 0 || n_feat <= 0 || k_parts <= 0) return 0;
-    return (int64_t)k_parts * agc::ls_wg_per_part(n_rows, k_parts) * n_feat;
+    return (int64_t)k_parts * agc::ls_wg_per_part(n_rows, n_feat, k_parts) * n_feat;
 }
 
 agc_status agc_ls_partial_gradients(const void* X_dev, int64_t n_rows, int n_feat, const float* y_dev,

@@ -70,7 +70,7 @@ hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& i
                          const float* scales, const Workspace& ws, float* ghat, hipStream_t stream);
 
 // Least-squares partial gradients G[p,:] = X_p^T (X_p w - y_p) (X bfloat16) and the descent update.
-int ls_wg_per_part(int64_t n_rows, int k_parts);
+int ls_wg_per_part(int64_t n_rows, int n_feat, int k_parts);
 hipError_t launch_ls_partial_gradients(const void* X, int64_t n_rows, int n_feat, const float* y,
                                        const float* w, int k_parts, float* G, int64_t ldg,
                                        float* resid, float* partial, hipStream_t stream);
