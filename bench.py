@@ -57,6 +57,84 @@ def stored_traffic(tag, kernel):
     return None, None
 
 
+def bench_lsq(args):
+    """--workload lsq: one step = partial gradients of the least-squares loss (MFMA kernel, X
+    resident in HBM) -> agc_step -> model update.  Not the headline workload: the line it prints
+    reports the rate at which the step streams X and the roofline of the partial-gradient kernel."""
+    import torch
+    from paper_2605_15890_amd import api
+    from paper_2605_15890_amd import inputs as I
+    cfg = I.CONFIGS["lsq"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n, k, F, N = cfg.n, cfg.k, cfg.d, cfg.extra["n_rows"]
+    p, bits, code, w = build_problem(cfg, api, "cyclic")
+    X, y, w_star = I.least_squares_torch(N, F, dev)
+    ctx = api.Context(n, k, F, scale_mode=api.AGC_SCALE_MAXABS)
+    ctx.agc_set_code(*code)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    G = api.padded_rows(k, F)
+    resid = torch.empty(N, dtype=torch.float32, device=dev)
+    ws = torch.empty(api.agc_ls_workspace_floats(N, F, k), dtype=torch.float32, device=dev)
+    beta = torch.zeros(F, dtype=torch.float32, device=dev)
+    lr = float(np.float32(0.5 / (N / F * (1 + np.sqrt(F / N)) ** 2)))
+    K, W = args.steps, args.warmup
+    masks = [I.arrival_mask(cfg, p, t) for t in range(W + K)]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+
+    def step(t, pair=None):
+        if pair:
+            pair[0].record()
+        api.agc_ls_partial_gradients(X, y, beta, k, G, resid, ws)     # on torch's current stream
+        if pair:
+            pair[1].record()
+        ctx.agc_step(G, bits, w, masks[t], cfg.philox_seed, t, codes, scales, ghat)
+        api.agc_gd_update(beta, ghat, lr)
+
+    for t in range(W):
+        step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        step(t, ev[t - W])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    ls_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))    # partial kernel + its small reduction
+    x_bytes = 2.0 * N * F
+    alg = x_bytes + 4.0 * N * 2 + 4.0 * F      # X once, y in, residual out, model in
+    traffic, traffic_src = stored_traffic("lsq", "ls_partial_gradients")
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import lsq as LS
+        rows = N // k
+        Xp = X[:rows].view(torch.int16).cpu().numpy().view(np.uint16)
+        yp, bh = y[:rows].cpu().numpy(), beta.cpu().numpy()
+        c0 = time.perf_counter()
+        LS.partial_gradients(Xp, yp, bh, 1)
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(2.0 * rows * F / (c1 - c0) / 1e9, 4), "unit": "GB/s",
+                        "cores": os.cpu_count(), "kind": "oracle",
+                        "sample": f"binary64 numpy partial gradient of one partition ({rows} of {N} samples), "
+                                  f"{c1 - c0:.2f} s wall"}
+    out = {
+        "metric": "least-squares GD step (partial gradients + encode/quantize/decode + update): GB/s of X streamed",
+        "value": round(x_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"lsq: N={N} samples, {F} features (bf16), k={k} partitions, n={n} workers, "
+                               f"s={cfg.s}, bits sum {int(bits.sum())}, cyclic code, maxabs scale"},
+        "roofline": {"kernel": "ls_partial_gradients", "bound": "hbm",
+                     "achieved": round(alg / (ls_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(alg / (ls_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": traffic_src, "avg_launch_ms": round(ls_ms, 4),
+                     "alg_bytes_per_launch": alg},
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +153,9 @@ def main():
         print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (the design for "
               "sharding along d is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "lsq":
+        return bench_lsq(args)
 
     import torch
     from paper_2605_15890_amd import api

@@ -25,7 +25,7 @@ class Config:
     k: int                      # partitions
     s: int                      # cyclic replication factor
     d: int                      # coordinates
-    law: str                    # "normal" | "layered" | "student_t3"
+    law: str                    # "normal" | "layered" | "student_t3" | "least_squares"
     p_law: tuple                # ("fixed", [..]) | ("uniform", lo, hi)
     bits_law: tuple             # ("fixed", [..]) | ("alloc", mean_bits) | ("uniform", lo, hi)
     iters: int
@@ -51,6 +51,10 @@ CONFIGS = {
                        extra={"blocks": 60, "log10_sigma": (-4.0, -1.0)}),
     "resnet50": Config(4, "resnet50", 64, 64, 4, 25_600_000, "student_t3", ("uniform", 0.05, 0.6),
                        ("alloc", 3), 100, extra={"scale": 1e-3}),
+    # end-to-end gradient descent on synthetic least squares; d is the feature dimension and the
+    # partial gradients come from least_squares_* below
+    "lsq": Config(5, "lsq", 32, 32, 3, 4096, "least_squares", ("uniform", 0.05, 0.5), ("alloc", 4), 500,
+                  extra={"n_rows": 1 << 20}),
 }
 
 

@@ -127,3 +127,64 @@ def test_end_to_end_loop_follows_the_oracle_loop():
     assert loss_d[-1] < 0.02 * loss_d[0], (loss_d[0], loss_d[-1])
     assert np.all(np.abs(loss_d - loss_o) <= 0.02 * loss_o), np.max(np.abs(loss_d - loss_o) / loss_o)
     assert _rel(beta_d.cpu().numpy(), beta_o.astype(np.float64)) < 0.02
+
+
+def test_full_size_loop_sampled_parity():
+    """N = 2^20 samples, 4096 features, k = n = 32, s = 3, 500 iterations, all on the GPU.  The
+    oracle cannot run that loop, so it checks, at three iterations, whole partitions of the
+    partial-gradient stage (binary64, given the GPU's current model) and the complete
+    encode/quantize/decode step on the GPU's partial gradients (bit for bit); the loss curve must
+    fall to the noise floor of the data."""
+    import torch
+    cfg = I.CONFIGS["lsq"]
+    n, k, s, F, N = cfg.n, cfg.k, cfg.s, cfg.d, cfg.extra["n_rows"]
+    dev = torch.device("cuda:0")
+    X, y_d, w_star = I.least_squares_torch(N, F, dev)
+    p = I.straggler_probs(cfg)
+    z_tot = cfg.bits_law[1] * n
+    bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    row_ptr, col, val, w = api.agc_build_cyclic_code(n, k, s, p, bits, pc)
+    csr = O.Csr(row_ptr, col, val, k)
+    ctx = api.Context(n, k, F, scale_mode=api.AGC_SCALE_MAXABS)
+    ctx.agc_set_code(row_ptr, col, val)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    G = api.padded_rows(k, F)
+    resid = torch.empty(N, dtype=torch.float32, device=dev)
+    ws = torch.empty(api.agc_ls_workspace_floats(N, F, k), dtype=torch.float32, device=dev)
+    beta = torch.zeros(F, dtype=torch.float32, device=dev)
+    lam = N / F * (1 + np.sqrt(F / N)) ** 2
+    lr = float(np.float32(0.5 / lam))
+    rows = N // k
+    losses = torch.zeros(cfg.iters, dtype=torch.float64, device=dev)
+    checked = 0
+    for t in range(cfg.iters):
+        mask = I.arrival_mask(cfg, p, t)
+        api.agc_ls_partial_gradients(X, y_d, beta, k, G, resid, ws)
+        ctx.agc_step(G, bits, w, mask, cfg.philox_seed, t, codes, scales, ghat)
+        losses[t] = 0.5 * (resid.double() ** 2).sum()
+        if t in (0, 7, cfg.iters - 1):
+            torch.cuda.synchronize()
+            print(f"[lsq] oracle check at iteration {t}", flush=True)
+            beta_h = beta.cpu().numpy()
+            G_h = G.cpu().numpy()
+            for part in ((0, 13, 31) if t == 0 else (t % k,)):
+                sl = slice(part * rows, (part + 1) * rows)
+                Xp = X[sl].view(torch.int16).cpu().numpy().view(np.uint16)
+                G_o, r_o = LS.partial_gradients(Xp, y_d[sl].cpu().numpy(), beta_h, 1)
+                assert _rel(resid[sl].cpu().numpy(), r_o) <= REL_L2_TOL, (t, part)
+                assert _rel(G_h[part], G_o[0]) <= REL_L2_TOL, (t, part)
+            _, o_scales, o_ghat = O.step(G_h, csr, bits, w, mask, cfg.philox_seed, t, O.SCALE_MAXABS)
+            assert np.array_equal(o_scales.view(np.uint32), scales.cpu().numpy().view(np.uint32)), t
+            assert np.array_equal(o_ghat.view(np.uint32), ghat.cpu().numpy().view(np.uint32)), t
+            checked += 1
+        api.agc_gd_update(beta, ghat, lr)
+    torch.cuda.synchronize()
+    ctx.close()
+    L = losses.cpu().numpy()
+    floor = 0.5 * N * 1e-4          # the noise in y has standard deviation 0.01
+    err = float(torch.linalg.norm(beta - w_star) / torch.linalg.norm(w_star))
+    print(f"[lsq] loss {L[0]:.4g} -> {L[-1]:.4g} (noise floor {floor:.4g}), |beta-w*|/|w*| = {err:.3g}", flush=True)
+    assert checked == 3
+    assert L[-1] < 1e-3 * L[0] and L[-1] < 3.0 * floor, (L[0], L[-1], floor)
+    assert err < 0.02
