@@ -151,6 +151,20 @@ agc_status agc_decode(agc_ctx *ctx, void *const *codes_dev, const float *scales_
                       const uint8_t *bits_host, const float *w_host, const uint8_t *mask_host,
                       float *ghat_dev, void *hip_stream);
 
+/*
+ * Two-track decoding (Sec. V, extension to adaptive optimizers; Appendix F): the master applies
+ * two decoding vectors to the same received codes.  g_hat is formed with w exactly as in
+ * agc_decode; g_hat2 is formed in the same way with v in place of w (same order, same
+ * rounding), from the same single read of the streams.
+ *
+ *   v_host     host, n floats: second-moment decoding vector (agc_second_moment_decoder)
+ *   ghat2_dev  device, d floats, 16-byte aligned, distinct from ghat_dev; overwritten
+ * Everything else as in agc_decode.
+ */
+agc_status agc_decode2(agc_ctx *ctx, void *const *codes_dev, const float *scales_dev,
+                       const uint8_t *bits_host, const float *w_host, const float *v_host,
+                       const uint8_t *mask_host, float *ghat_dev, float *ghat2_dev, void *hip_stream);
+
 /* One whole pass: agc_encode_quantize followed by agc_decode on the same stream. */
 agc_status agc_step(agc_ctx *ctx, const float *G_dev, int64_t ldg, const uint8_t *bits_host,
                     const float *w_host, const uint8_t *mask_host, uint64_t seed, uint64_t step,
@@ -189,6 +203,16 @@ agc_status agc_ls_partial_gradients(const void *X_dev, int64_t n_rows, int n_fea
 /* Gradient-descent update of Sec. II-A: beta <- beta - lr * g_hat (one fused multiply-add per
  * coordinate), device pointers, d floats each. */
 agc_status agc_gd_update(float *beta_dev, const float *ghat_dev, float lr, int64_t d, void *hip_stream);
+/* Adam step t (t >= 1) that consumes the two tracks of agc_decode2 (Sec. V; update ratio of
+ * Appendix F): the first-moment average takes g_hat, the second-moment average takes the
+ * square of g_hat2; binary32 throughout:
+ *   m1 <- beta1*m1 + (1-beta1)*g_hat;  m2 <- beta2*m2 + (1-beta2)*g_hat2^2;
+ *   beta <- beta - lr * (m1/(1-beta1^t)) / (sqrt(m2/(1-beta2^t)) + eps).
+ * The bias corrections and eps are the customary ones of the optimizer; the paper prints only
+ * the ratio.  All pointers device, d floats each; beta, m1, m2 updated in place. */
+agc_status agc_adam_update(float *beta_dev, float *m1_dev, float *m2_dev, const float *ghat_dev,
+                           const float *ghat2_dev, float lr, float beta1, float beta2, float eps,
+                           int64_t t, int64_t d, void *hip_stream);
 
 /* Measurement utility, not part of the method: a plain copy kernel that reads `bytes` and
  * writes `bytes` (device pointers, 16-byte aligned, bytes a multiple of 16).  Profiling runs
@@ -239,6 +263,15 @@ agc_status agc_build_cyclic_code(int n, int k, int s, const double *p, const uin
 agc_status agc_check_unbiased(int n, int k, const int32_t *row_ptr, const int32_t *col,
                               const float *val, const float *w, const double *p, double tol,
                               double *residual);
+
+/* Second-moment decoding vector of the two-track decode (Sec. V, closed form below the
+ * bias-variance objective): with A_i the i-th row sum of the code and c_i = (p_i+phi(z_i))/(1-p_i),
+ *   v_i = k * Lambda / ((p_i + phi(z_i)) * A_i * (1 + Lambda * sum_m 1/c_m)),
+ * k being the number of columns of the code (the count the bias term sums over).  Lambda > 0
+ * weighs squared bias against variance.  v_out: host, n floats. */
+agc_status agc_second_moment_decoder(int n, int k, const int32_t *row_ptr, const int32_t *col,
+                                     const float *val, const double *p, const uint8_t *bits,
+                                     double phi_coef, double Lambda, float *v_out);
 
 #ifdef __cplusplus
 }

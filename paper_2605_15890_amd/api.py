@@ -21,6 +21,7 @@ KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
+    "agc_decode2", "agc_adam_update", "agc_second_moment_decoder",
     "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
@@ -77,6 +78,14 @@ def load():
     L.agc_encode_quantize.restype = C.c_int
     L.agc_decode.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _u8p, _vp, _vp]
     L.agc_decode.restype = C.c_int
+    L.agc_decode2.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _f32p, _u8p, _vp, _vp, _vp]
+    L.agc_decode2.restype = C.c_int
+    L.agc_adam_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, C.c_float, C.c_float,
+                                  C.c_int64, C.c_int64, _vp]
+    L.agc_adam_update.restype = C.c_int
+    L.agc_second_moment_decoder.argtypes = [C.c_int, C.c_int, _i32p, _i32p, _f32p, _f64p, _u8p, C.c_double,
+                                            C.c_double, _f32p]
+    L.agc_second_moment_decoder.restype = C.c_int
     L.agc_step.argtypes = [_vp, _vp, C.c_int64, _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64,
                            C.POINTER(_vp), _vp, _vp, _vp]
     L.agc_step.restype = C.c_int
@@ -198,6 +207,20 @@ def agc_check_unbiased(k, row_ptr, col, val, w, p, tol=1e-5):
     return st == AGC_OK, float(res.value)
 
 
+def agc_second_moment_decoder(k, row_ptr, col, val, p, bits, phi_coef, lam):
+    """Second decoding vector v* of the two-track decode (float32, n entries)."""
+    row_ptr, col, val = _np(row_ptr, np.int32), _np(col, np.int32), _np(val, np.float32)
+    p, bits = _np(p, np.float64), _np(bits, np.uint8)
+    n = len(row_ptr) - 1
+    v = np.zeros(n, dtype=np.float32)
+    st = load().agc_second_moment_decoder(n, int(k), _ptr(row_ptr, _i32p), _ptr(col, _i32p), _ptr(val, _f32p),
+                                          _ptr(p, _f64p), _ptr(bits, _u8p), float(phi_coef), float(lam),
+                                          _ptr(v, _f32p))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_second_moment_decoder")
+    return v
+
+
 # --------------------------------------------------------------------------- hot path
 def _stream_handle(stream):
     if stream is None:
@@ -275,6 +298,16 @@ class Context:
             self._check(st)
         return st
 
+    def agc_decode2(self, codes, scales, bits, w, v, mask, ghat, ghat2, stream=None, check=True):
+        bits, w, v, mask = _np(bits, np.uint8), _np(w, np.float32), _np(v, np.float32), _np(mask, np.uint8)
+        st = self.lib.agc_decode2(self.h, self._code_ptrs(codes), C.c_void_p(scales.data_ptr()),
+                                  _ptr(bits, _u8p), _ptr(w, _f32p), _ptr(v, _f32p), _ptr(mask, _u8p),
+                                  C.c_void_p(ghat.data_ptr()), C.c_void_p(ghat2.data_ptr()),
+                                  _stream_handle(stream))
+        if check:
+            self._check(st)
+        return st
+
     def agc_step(self, G, bits, w, mask, seed, step, codes, scales, ghat, stream=None, check=True):
         bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
         st = self.lib.agc_step(self.h, C.c_void_p(G.data_ptr()), G.stride(0), _ptr(bits, _u8p), _ptr(w, _f32p),
@@ -315,6 +348,15 @@ def agc_gd_update(beta, ghat, lr, stream=None):
                               beta.numel(), _stream_handle(stream))
     if st != AGC_OK:
         raise AgcError(st, "agc_gd_update")
+
+
+def agc_adam_update(beta, m1, m2, ghat, ghat2, lr, beta1, beta2, eps, t, stream=None):
+    st = load().agc_adam_update(C.c_void_p(beta.data_ptr()), C.c_void_p(m1.data_ptr()), C.c_void_p(m2.data_ptr()),
+                                C.c_void_p(ghat.data_ptr()), C.c_void_p(ghat2.data_ptr()), float(lr),
+                                float(beta1), float(beta2), float(eps), int(t), beta.numel(),
+                                _stream_handle(stream))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_adam_update")
 
 
 def agc_calibration_copy(dst, src, nbytes, stream=None):

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <cmath>
 #include <vector>
 
 #include "../../include/agc.h"
@@ -199,6 +200,7 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     }
     if (e == hipSuccess) e = dev_alloc(&c->ws.wq, (size_t)n);
     if (e == hipSuccess) e = dev_alloc(&c->ws.wd, (size_t)n);
+    if (e == hipSuccess) e = dev_alloc(&c->ws.coef2, (size_t)n);
     if (e != hipSuccess) {
         agc_destroy(c);
         return fail(nullptr, e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP,
@@ -218,6 +220,7 @@ void agc_destroy(agc_ctx* c)
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
     if (c->ws.wq) (void)hipFree(c->ws.wq);
     if (c->ws.wd) (void)hipFree(c->ws.wd);
+    if (c->ws.coef2) (void)hipFree(c->ws.coef2);
     for (auto& ring : c->events)
         for (auto& ep : ring) {
             if (ep.beg) (void)hipEventDestroy(ep.beg);
@@ -342,6 +345,51 @@ agc_status agc_decode(agc_ctx* c, void* const* codes, const float* scales, const
     hipError_t e = agc::launch_decode(c->n, n_arrived, c->d, ds, scales, c->ws, ghat, stream);
     if (e != hipSuccess) return hip_fail(c, e, "decode launch");
     return t.end();
+}
+
+agc_status agc_decode2(agc_ctx* c, void* const* codes, const float* scales, const uint8_t* bits,
+                       const float* w, const float* v, const uint8_t* mask, float* ghat, float* ghat2,
+                       void* hip_stream)
+{
+    if (!c) return AGC_EINVAL;
+    if (!codes || !scales || !bits || !w || !v || !mask || !ghat || !ghat2)
+        return fail(c, AGC_EINVAL, "null argument");
+    if ((reinterpret_cast<uintptr_t>(ghat) & 15u) || (reinterpret_cast<uintptr_t>(ghat2) & 15u))
+        return fail(c, AGC_EALIGN, "ghat_dev / ghat2_dev is not 16-byte aligned");
+    if (ghat == ghat2) return fail(c, AGC_EINVAL, "ghat_dev and ghat2_dev must be different buffers");
+    agc_status st = check_bits(c, bits);
+    if (st != AGC_OK) return st;
+    st = check_streams(c, codes);
+    if (st != AGC_OK) return st;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    agc::DecodeStreams ds{};
+    agc::DecodeSecond d2{};
+    int n_arrived = 0;
+    for (int i = 0; i < c->n; ++i) {
+        ds.codes[i] = codes[i];
+        ds.w[i] = w[i];
+        d2.v[i] = v[i];
+        ds.bits[i] = d2.bits[i] = bits[i];
+        ds.slot[i] = d2.slot[i] = mask[i] ? (uint16_t)n_arrived++ : (uint16_t)0xFFFF;
+    }
+    KernelTimer t{c, 3, stream};
+    if ((st = t.begin()) != AGC_OK) return st;
+    hipError_t e = agc::launch_decode2(c->n, n_arrived, c->d, ds, d2, scales, c->ws, ghat, ghat2, stream);
+    if (e != hipSuccess) return hip_fail(c, e, "two-track decode launch");
+    return t.end();
+}
+
+agc_status agc_adam_update(float* beta_dev, float* m1_dev, float* m2_dev, const float* ghat_dev,
+                           const float* ghat2_dev, float lr, float beta1, float beta2, float eps,
+                           int64_t t, int64_t d, void* hip_stream)
+{
+    if (!beta_dev || !m1_dev || !m2_dev || !ghat_dev || !ghat2_dev || d <= 0 || t <= 0) return AGC_EINVAL;
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f)) return AGC_EINVAL;
+    const float corr1 = (float)(1.0 - std::pow((double)beta1, (double)t));
+    const float corr2 = (float)(1.0 - std::pow((double)beta2, (double)t));
+    hipError_t e = agc::launch_adam_update(beta_dev, m1_dev, m2_dev, ghat_dev, ghat2_dev, lr, beta1, beta2, eps,
+                                           corr1, corr2, d, reinterpret_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? AGC_OK : AGC_EHIP;
 }
 
 agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits, const float* w,

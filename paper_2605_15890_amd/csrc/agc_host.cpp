@@ -315,4 +315,29 @@ agc_status agc_check_unbiased(int n, int k, const int32_t* row_ptr, const int32_
     return worst <= tol ? AGC_OK : AGC_EINVAL;
 }
 
+agc_status agc_second_moment_decoder(int n, int k, const int32_t* row_ptr, const int32_t* col,
+                                     const float* val, const double* p, const uint8_t* bits,
+                                     double phi_coef, double lambda, float* v)
+{
+    if (!row_ptr || !col || !val || !p || !bits || !v || n <= 0 || k <= 0 || !(lambda > 0.0)) return AGC_EINVAL;
+    // stationarity of  lambda * (k - sum_i u_i)^2 + sum_i c_i u_i^2  in u_i = (1-p_i) v_i A_i,
+    // A_i the row sum of the code, c_i = (p_i + phi(z_i)) / (1 - p_i)
+    double inv_c_sum = 0.0;
+    for (int i = 0; i < n; ++i) {
+        if (!(p[i] >= 0.0 && p[i] < 1.0)) return AGC_EINVAL;
+        inv_c_sum += (1.0 - p[i]) / (p[i] + phi_of((double)bits[i], phi_coef));
+    }
+    for (int i = 0; i < n; ++i) {
+        double row_sum = 0.0;
+        for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+            if (col[e] < 0 || col[e] >= k) return AGC_ESHAPE;
+            row_sum += (double)val[e];
+        }
+        if (row_sum == 0.0) return AGC_EINVAL;
+        v[i] = (float)((double)k * lambda /
+                       ((p[i] + phi_of((double)bits[i], phi_coef)) * row_sum * (1.0 + lambda * inv_c_sum)));
+    }
+    return AGC_OK;
+}
+
 }  // extern "C"

@@ -38,6 +38,7 @@ struct Workspace {
     double* super_sq;     // [n][nsuper]
     WorkerQ* wq;          // [n]  written by the scale finalize
     WorkerD* wd;          // [n]  arrived workers, compacted, written by the decode prologue
+    float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     int64_t nseg, ngroup, nsuper;
 };
 
@@ -51,6 +52,12 @@ struct DecodeStreams {     // host arrays of the decode call, as kernel argument
     float w[kArgWorkers];
     uint8_t bits[kArgWorkers];
     uint16_t slot[kArgWorkers];  // position among the arrived workers, 0xFFFF for a straggler
+};
+
+struct DecodeSecond {      // second decoding vector of the two-track decode (Sec. V)
+    float v[kArgWorkers];
+    uint8_t bits[kArgWorkers];
+    uint16_t slot[kArgWorkers];
 };
 
 // K1: per-segment partials of every worker's scale.  scale_mode: 0 Euclidean, 1 max-abs.
@@ -68,6 +75,14 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
 // weighted sum.
 hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
                          const float* scales, const Workspace& ws, float* ghat, hipStream_t stream);
+// Two-track variant: the same read of the codes feeds a second weighted sum with weights v.
+hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& in, const DecodeSecond& second,
+                          const float* scales, const Workspace& ws, float* ghat, float* ghat2,
+                          hipStream_t stream);
+// Adam update that takes its first moment from ghat and its second moment from ghat2.
+hipError_t launch_adam_update(float* beta, float* m1, float* m2, const float* ghat, const float* ghat2,
+                              float lr, float beta1, float beta2, float eps, float corr1, float corr2,
+                              int64_t d, hipStream_t stream);
 
 // Least-squares partial gradients G[p,:] = X_p^T (X_p w - y_p) (X bfloat16) and the descent update.
 int ls_wg_per_part(int64_t n_rows, int n_feat, int k_parts);

@@ -465,9 +465,23 @@ __global__ __launch_bounds__(kWgThreads) void k_decode_table(int n, DecodeStream
     wd[slot] = WorkerD{in.codes[i], (float)(((double)in.w[i] * (double)scales[i]) / L), (uint32_t)b};
 }
 
-template <int B>
-__device__ __forceinline__ void decode_words(const global_u32* __restrict__ src, float coef,
-                                             float (&acc)[kDecCoords])
+// second table of the two-track decode: weight of one grid unit of worker i under the
+// second decoding vector, v_i * scale_i / L_i, same rounding as the first
+__global__ __launch_bounds__(kWgThreads) void k_decode_table2(int n, DecodeSecond in, const float* scales,
+                                                              float* coef2)
+{
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    const uint32_t slot = in.slot[i];
+    if (slot == 0xFFFFu) return;
+    const int b = in.bits[i];
+    const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+    coef2[slot] = (float)(((double)in.v[i] * (double)scales[i]) / L);
+}
+
+template <int B, bool TWO>
+__device__ __forceinline__ void decode_words(const global_u32* __restrict__ src, float coef, float coef2,
+                                             float (&acc)[kDecCoords], float (&acc2)[TWO ? kDecCoords : 1])
 {
     uint32_t w[B];
 #pragma unroll
@@ -492,6 +506,7 @@ __device__ __forceinline__ void decode_words(const global_u32* __restrict__ src,
             v = __uint_as_float(__float_as_uint((float)level) | sign);
         }
         acc[q] = fmaf(coef, v, acc[q]);
+        if (TWO) acc2[TWO ? q : 0] = fmaf(coef2, v, acc2[TWO ? q : 0]);
     }
 }
 
@@ -499,49 +514,61 @@ struct DecodeArgs {
     int n_arrived;
     int64_t d;
     float* ghat;
+    float* ghat2;  // second track (two-track decode only)
 };
 
-__global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict__ wd, DecodeArgs a)
+__device__ __forceinline__ void store_coords(float* dst, const float (&acc)[kDecCoords], int64_t m0, int64_t d)
 {
-    const int64_t t = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
-    const int64_t m0 = t * kDecCoords;
-    if (m0 >= a.d) return;
-    float acc[kDecCoords];
-#pragma unroll
-    for (int q = 0; q < kDecCoords; ++q) acc[q] = 0.f;
-    for (int e = 0; e < a.n_arrived; ++e) {
-        const WorkerD wk = wd[e];  // wave-uniform: one scalar 16-byte load
-        const int b = (int)wk.bits;
-        const global_u32* src = (const global_u32*)wk.codes + t * b;
-        switch (b) {
-            case 1: decode_words<1>(src, wk.coef, acc); break;
-            case 2: decode_words<2>(src, wk.coef, acc); break;
-            case 3: decode_words<3>(src, wk.coef, acc); break;
-            case 4: decode_words<4>(src, wk.coef, acc); break;
-            case 5: decode_words<5>(src, wk.coef, acc); break;
-            case 6: decode_words<6>(src, wk.coef, acc); break;
-            case 7: decode_words<7>(src, wk.coef, acc); break;
-            case 8: decode_words<8>(src, wk.coef, acc); break;
-            case 9: decode_words<9>(src, wk.coef, acc); break;
-            case 10: decode_words<10>(src, wk.coef, acc); break;
-            case 11: decode_words<11>(src, wk.coef, acc); break;
-            case 12: decode_words<12>(src, wk.coef, acc); break;
-            case 13: decode_words<13>(src, wk.coef, acc); break;
-            case 14: decode_words<14>(src, wk.coef, acc); break;
-            case 15: decode_words<15>(src, wk.coef, acc); break;
-            default: decode_words<16>(src, wk.coef, acc); break;
-        }
-    }
-    float* dst = a.ghat + m0;
-    if (m0 + kDecCoords <= a.d) {
+    if (m0 + kDecCoords <= d) {
 #pragma unroll
         for (int q = 0; q < kDecCoords; q += 4)
             *reinterpret_cast<float4*>(dst + q) = make_float4(acc[q], acc[q + 1], acc[q + 2], acc[q + 3]);
     } else {
 #pragma unroll
         for (int q = 0; q < kDecCoords; ++q)
-            if (m0 + q < a.d) dst[q] = acc[q];
+            if (m0 + q < d) dst[q] = acc[q];
     }
+}
+
+template <bool TWO>
+__global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict__ wd,
+                                                       const float* __restrict__ coef2, DecodeArgs a)
+{
+    const int64_t t = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
+    const int64_t m0 = t * kDecCoords;
+    if (m0 >= a.d) return;
+    float acc[kDecCoords];
+    float acc2[TWO ? kDecCoords : 1];
+#pragma unroll
+    for (int q = 0; q < kDecCoords; ++q) acc[q] = 0.f;
+#pragma unroll
+    for (int q = 0; q < (TWO ? kDecCoords : 1); ++q) acc2[q] = 0.f;
+    for (int e = 0; e < a.n_arrived; ++e) {
+        const WorkerD wk = wd[e];  // wave-uniform: one scalar 16-byte load
+        const float c2 = TWO ? coef2[e] : 0.f;
+        const int b = (int)wk.bits;
+        const global_u32* src = (const global_u32*)wk.codes + t * b;
+        switch (b) {
+            case 1: decode_words<1, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 2: decode_words<2, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 3: decode_words<3, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 4: decode_words<4, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 5: decode_words<5, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 6: decode_words<6, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 7: decode_words<7, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 8: decode_words<8, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 9: decode_words<9, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 10: decode_words<10, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 11: decode_words<11, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 12: decode_words<12, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 13: decode_words<13, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 14: decode_words<14, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 15: decode_words<15, TWO>(src, wk.coef, c2, acc, acc2); break;
+            default: decode_words<16, TWO>(src, wk.coef, c2, acc, acc2); break;
+        }
+    }
+    store_coords(a.ghat + m0, acc, m0, a.d);
+    if constexpr (TWO) store_coords(a.ghat2 + m0, acc2, m0, a.d);
 }
 
 hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
@@ -550,10 +577,56 @@ hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& i
     hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, ws.wd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    DecodeArgs a{n_arrived, d, ghat};
+    DecodeArgs a{n_arrived, d, ghat, nullptr};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    hipLaunchKernelGGL(k_decode, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, a);
+    hipLaunchKernelGGL(k_decode<false>, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd,
+                       static_cast<const float*>(nullptr), a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& in, const DecodeSecond& second,
+                          const float* scales, const Workspace& ws, float* ghat, float* ghat2,
+                          hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, ws.wd);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_decode_table2, dim3(1), dim3(kWgThreads), 0, stream, n, second, scales, ws.coef2);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    DecodeArgs a{n_arrived, d, ghat, ghat2};
+    const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
+    const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
+    hipLaunchKernelGGL(k_decode<true>, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd,
+                       static_cast<const float*>(ws.coef2), a);
+    return hipGetLastError();
+}
+
+// Adam with the two-track estimates (Sec. V): first moment from the unbiased estimate, second
+// moment from the square of the variance-reduced one.  corr1 = 1 - beta1^t, corr2 = 1 - beta2^t.
+__global__ __launch_bounds__(kWgThreads) void k_adam_update(float* beta, float* m1, float* m2,
+                                                            const float* __restrict__ ghat,
+                                                            const float* __restrict__ ghat2, float lr, float beta1,
+                                                            float beta2, float eps, float corr1, float corr2,
+                                                            int64_t d)
+{
+    const int64_t i = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
+    if (i >= d) return;
+    const float g = ghat[i], h = ghat2[i];
+    const float a = fmaf(beta1, m1[i], (1.0f - beta1) * g);
+    const float b = fmaf(beta2, m2[i], (1.0f - beta2) * (h * h));
+    m1[i] = a;
+    m2[i] = b;
+    beta[i] = beta[i] - lr * (a / corr1) / (sqrtf(b / corr2) + eps);
+}
+
+hipError_t launch_adam_update(float* beta, float* m1, float* m2, const float* ghat, const float* ghat2,
+                              float lr, float beta1, float beta2, float eps, float corr1, float corr2,
+                              int64_t d, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_adam_update, dim3((unsigned)((d + kWgThreads - 1) / kWgThreads)), dim3(kWgThreads), 0,
+                       stream, beta, m1, m2, ghat, ghat2, lr, beta1, beta2, eps, corr1, corr2, d);
     return hipGetLastError();
 }
 

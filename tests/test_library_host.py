@@ -139,3 +139,27 @@ def test_cyclic_code_matches_oracle():
         assert ok
     with pytest.raises(api.AgcError):
         api.agc_build_cyclic_code(4, 5, 2, [0.1] * 4, [2] * 4, 0.2)
+
+
+def test_second_moment_decoder_matches_oracle_and_beats_unbiased_decoder():
+    """Closed form of the two-track decoder (Sec. V): the host routine against the oracle's
+    formula (itself pinned by numerical minimisation), and Proposition 3's dominance."""
+    rng = np.random.default_rng(23)
+    for n, s in [(4, 2), (16, 3), (64, 4)]:
+        p = rng.uniform(0.05, 0.6, n)
+        bits = rng.integers(2, 9, n).astype(np.uint8)
+        row_ptr, col, val, w = api.agc_build_cyclic_code(n, n, s, p, bits, 0.2)
+        B = np.zeros((n, n))
+        for i in range(n):
+            B[i, col[row_ptr[i]:row_ptr[i + 1]]] = val[row_ptr[i]:row_ptr[i + 1]]
+        for lam in (0.05, 1.0, 50.0):
+            v = api.agc_second_moment_decoder(n, row_ptr, col, val, p, bits, 0.2, lam)
+            v_o = D.second_moment_decoder(p, bits, 0.2, B, lam)
+            assert np.allclose(v, v_o, rtol=2e-7 * 4, atol=0)
+            m_v = D.second_moment_objective(v.astype(np.float64), p, bits, 0.2, B, lam)
+            m_w = D.second_moment_objective(w.astype(np.float64), p, bits, 0.2, B, lam)
+            assert m_v <= m_w
+            var = lambda u: D.second_moment_objective(u, p, bits, 0.2, B, 0.0)      # variance part alone
+            assert var(v.astype(np.float64)) <= var(w.astype(np.float64)) * (1 + 1e-6)
+    with pytest.raises(api.AgcError):
+        api.agc_second_moment_decoder(4, [0, 1, 2, 3, 4], [0, 1, 2, 3], [1, 1, 1, 1], [0.1] * 4, [4] * 4, 0.2, 0.0)
