@@ -445,6 +445,131 @@ void agc_oracle_step(int n, int64_t d, const float *G, int64_t ldg,
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Bucket-wise granularity            (Sec. II-B: the extension the paper calls */
+/* straightforward; one scale per 256-coordinate bucket instead of one per      */
+/* vector, at the price of transmitting d/256 scales per worker)                */
+/* ------------------------------------------------------------------------- */
+/* Readings fixed here (the paper gives no arithmetic for the extension):
+ *   bucket u      = coordinates [256u, 256u+256) that are < d;
+ *   scale         = largest magnitude in the bucket (mode 1), or the Euclidean
+ *                   norm of the bucket (mode 0): levels 0 and 1 of the binary64
+ *                   tree above, square root, one rounding to binary32;
+ *   multiplier    = L*2^16 / scale (b >= 2), 2^15 / scale (b == 1): ONE binary32
+ *                   division (the dividend is exact in binary32); 0 when the
+ *                   scale is 0 or the quotient overflows;
+ *   rounding rule, draws, codes, payload: exactly as for the global scale;
+ *   decode weight = wl_i * scale_iu, ONE binary32 product, with
+ *                   wl_i = (float)((double)w_i / L_i);  then as before: arrived
+ *                   workers ascending, one fused multiply-add each from 0.     */
+int64_t agc_oracle_num_buckets(int64_t d) { return (d + 255) / 256; }
+
+/* scale of one bucket given as its own short array fb[0..cnt), cnt <= 256 */
+static float bucket_scale_local(const float *fb, int cnt, int scale_mode)
+{
+    if (scale_mode == 0) return (float)sqrt(l2_block(fb, cnt, 0));
+    return agc_oracle_scale_maxabs(fb, cnt);
+}
+
+float agc_oracle_bucket_scale(const float *f, int64_t d, int64_t u, int scale_mode)
+{
+    int64_t a = u * 256, b = a + 256 < d ? a + 256 : d;
+    return bucket_scale_local(f + a, (int)(b - a), scale_mode);
+}
+
+float agc_oracle_inv16_bucket(float scale, int bits)
+{
+    if (!(scale > 0.0f)) return 0.0f;
+    float num = bits >= 2 ? (float)agc_oracle_levels(bits) * 65536.0f : 32768.0f;
+    float q = num / scale;
+    if (!(q <= 3.402823466e+38f)) return 0.0f;
+    return q;
+}
+
+float agc_oracle_wl_bucket(float w, int bits)
+{
+    return (float)((double)w / (double)agc_oracle_levels(bits));
+}
+
+/* scales [nb] and unpacked codes [m1-m0] of worker i for the buckets that cover
+ * [m0, m1); m0 must be a multiple of 256.  scales_out may be NULL. */
+void agc_oracle_codes_bucket_range(const float *G, int64_t ldg, const int32_t *row_ptr,
+                                   const int32_t *col, const float *val, int i, int bits,
+                                   int scale_mode, uint64_t seed, uint64_t step, int64_t d,
+                                   int64_t m0, int64_t m1, uint32_t *codes_out,
+                                   float *scales_out)
+{
+    float f[256];
+    for (int64_t u = m0 / 256; u * 256 < m1; ++u) {
+        int64_t a = u * 256, b = a + 256 < d ? a + 256 : d;
+        /* the bucket's scale needs the whole bucket, also past m1 */
+        agc_oracle_encode_range(G, ldg, row_ptr, col, val, i, a, b, f);
+        float scale = bucket_scale_local(f, (int)(b - a), scale_mode);
+        if (scales_out) scales_out[u - m0 / 256] = scale;
+        float inv16 = agc_oracle_inv16_bucket(scale, bits);
+        for (int64_t m = a; m < b && m < m1; ++m) {
+            uint32_t u16, r2;
+            agc_oracle_draw(seed, step, (uint32_t)i, (uint64_t)m, &u16, &r2);
+            codes_out[m - m0] = agc_oracle_quantize_one(f[m - a], inv16, bits, u16, r2);
+        }
+    }
+}
+
+/* encode + quantize + pack for all workers; scales_out is n x nb, row-major */
+void agc_oracle_encode_quantize_bucket(int n, int64_t d, const float *G, int64_t ldg,
+                                       const int32_t *row_ptr, const int32_t *col,
+                                       const float *val, const uint8_t *bits,
+                                       uint64_t seed, uint64_t step, int scale_mode,
+                                       uint8_t *const *streams_out, float *scales_out)
+{
+    int64_t nb = agc_oracle_num_buckets(d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < n; ++i) {
+        uint32_t *codes = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(d > 0 ? d : 1));
+        agc_oracle_codes_bucket_range(G, ldg, row_ptr, col, val, i, bits[i], scale_mode, seed,
+                                      step, d, 0, d, codes, scales_out + (int64_t)i * nb);
+        agc_oracle_pack(codes, d, bits[i], streams_out[i]);
+        free(codes);
+    }
+}
+
+void agc_oracle_decode_bucket_range(int n, const uint8_t *const *streams,
+                                    const float *scales, int64_t nb, const uint8_t *bits,
+                                    const float *w, const uint8_t *mask, int64_t m0,
+                                    int64_t m1, float *ghat_out)
+{
+    for (int64_t m = m0; m < m1; ++m) {
+        float acc = 0.0f;
+        for (int i = 0; i < n; ++i) {
+            if (!mask[i]) continue;
+            float coef = agc_oracle_wl_bucket(w[i], bits[i]) * scales[(int64_t)i * nb + m / 256];
+            float v = agc_oracle_code_value(
+                agc_oracle_unpack_one(streams[i], bits[i], m), bits[i]);
+            acc = fmaf(coef, v, acc);
+        }
+        ghat_out[m - m0] = acc;
+    }
+}
+
+void agc_oracle_step_bucket(int n, int64_t d, const float *G, int64_t ldg,
+                            const int32_t *row_ptr, const int32_t *col, const float *val,
+                            const uint8_t *bits, const float *w, const uint8_t *mask,
+                            uint64_t seed, uint64_t step, int scale_mode,
+                            uint8_t *const *streams_out, float *scales_out, float *ghat_out)
+{
+    agc_oracle_encode_quantize_bucket(n, d, G, ldg, row_ptr, col, val, bits, seed, step,
+                                      scale_mode, streams_out, scales_out);
+    int64_t nb = agc_oracle_num_buckets(d);
+    int64_t chunk = 4096;
+    int64_t nchunks = (d + chunk - 1) / chunk;
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < nchunks; ++c) {
+        int64_t m0 = c * chunk, m1 = m0 + chunk < d ? m0 + chunk : d;
+        agc_oracle_decode_bucket_range(n, (const uint8_t *const *)streams_out, scales_out, nb,
+                                       bits, w, mask, m0, m1, ghat_out + m0);
+    }
+}
+
 int agc_oracle_threads(void)
 {
 #ifdef _OPENMP

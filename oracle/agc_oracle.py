@@ -72,6 +72,27 @@ def lib():
                                                  _f32p, _u8p, C.c_uint64, C.c_uint64, C.c_int,
                                                  _f32p, C.POINTER(_u8p), _f32p]
         L.agc_oracle_encode_quantize.restype = None
+        L.agc_oracle_bucket_scale.argtypes = [_f32p, C.c_int64, C.c_int64, C.c_int]
+        L.agc_oracle_bucket_scale.restype = C.c_float
+        L.agc_oracle_inv16_bucket.argtypes = [C.c_float, C.c_int]
+        L.agc_oracle_inv16_bucket.restype = C.c_float
+        L.agc_oracle_wl_bucket.argtypes = [C.c_float, C.c_int]
+        L.agc_oracle_wl_bucket.restype = C.c_float
+        L.agc_oracle_codes_bucket_range.argtypes = [_f32p, C.c_int64, _i32p, _i32p, _f32p, C.c_int, C.c_int,
+                                                    C.c_int, C.c_uint64, C.c_uint64, C.c_int64, C.c_int64,
+                                                    C.c_int64, _u32p, _f32p]
+        L.agc_oracle_codes_bucket_range.restype = None
+        L.agc_oracle_encode_quantize_bucket.argtypes = [C.c_int, C.c_int64, _f32p, C.c_int64, _i32p, _i32p,
+                                                        _f32p, _u8p, C.c_uint64, C.c_uint64, C.c_int,
+                                                        C.POINTER(_u8p), _f32p]
+        L.agc_oracle_encode_quantize_bucket.restype = None
+        L.agc_oracle_decode_bucket_range.argtypes = [C.c_int, C.POINTER(_u8p), _f32p, C.c_int64, _u8p, _f32p,
+                                                     _u8p, C.c_int64, C.c_int64, _f32p]
+        L.agc_oracle_decode_bucket_range.restype = None
+        L.agc_oracle_step_bucket.argtypes = [C.c_int, C.c_int64, _f32p, C.c_int64, _i32p, _i32p, _f32p,
+                                             _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64, C.c_int,
+                                             C.POINTER(_u8p), _f32p, _f32p]
+        L.agc_oracle_step_bucket.restype = None
         L.agc_oracle_step.argtypes = [C.c_int, C.c_int64, _f32p, C.c_int64, _i32p, _i32p, _f32p,
                                       _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64, C.c_int,
                                       C.POINTER(_u8p), _f32p, _f32p]
@@ -103,6 +124,76 @@ def _u8(a):
 def _u32(a):
     a = np.ascontiguousarray(a, dtype=np.uint32)
     return a, a.ctypes.data_as(_u32p)
+
+
+# ------------------------------------------------------------------ bucket-wise scales
+BUCKET = 256
+
+
+def num_buckets(d):
+    return (int(d) + BUCKET - 1) // BUCKET
+
+
+def bucket_scale(f, u, scale_mode):
+    f, fp = _f32(f)
+    return float(lib().agc_oracle_bucket_scale(fp, f.size, int(u), int(scale_mode)))
+
+
+def inv16_bucket(scale, bits):
+    return float(lib().agc_oracle_inv16_bucket(float(scale), int(bits)))
+
+
+def wl_bucket(w, bits):
+    return float(lib().agc_oracle_wl_bucket(float(w), int(bits)))
+
+
+def codes_bucket_range(G, csr, i, bits_i, scale_mode, seed, step, m0, m1):
+    """Unpacked codes of worker i on [m0, m1) (m0 a multiple of 256) and the scales of the
+    buckets that cover the range."""
+    G, gp = _f32(G)
+    d = G.shape[1]
+    assert m0 % BUCKET == 0
+    rp, cp, vp = csr.ptrs()
+    out = np.zeros(m1 - m0, dtype=np.uint32)
+    sc = np.zeros(num_buckets(m1) - m0 // BUCKET, dtype=np.float32)
+    lib().agc_oracle_codes_bucket_range(gp, G.strides[0] // 4, rp, cp, vp, int(i), int(bits_i),
+                                        int(scale_mode), int(seed), int(step), d, int(m0), int(m1),
+                                        out.ctypes.data_as(_u32p), sc.ctypes.data_as(_f32p))
+    return out, sc
+
+
+def decode_bucket(streams, scales, bits, w, mask, d, m0=0, m1=None):
+    """scales: (n, num_buckets(d)) float32."""
+    m1 = d if m1 is None else m1
+    n = len(streams)
+    sp, keep = _stream_ptrs(streams)
+    sc, scp = _f32(scales)
+    assert sc.shape == (n, num_buckets(d))
+    b, bp = _u8(bits)
+    ww, wp = _f32(w)
+    mk, mp = _u8(mask)
+    out = np.zeros(m1 - m0, dtype=np.float32)
+    lib().agc_oracle_decode_bucket_range(n, sp, scp, num_buckets(d), bp, wp, mp, int(m0), int(m1),
+                                         out.ctypes.data_as(_f32p))
+    return out
+
+
+def step_bucket(G, csr, bits, w, mask, seed, step_, scale_mode):
+    """One whole pass with one scale per 256-coordinate bucket.  Returns (streams, scales (n, nb), ghat)."""
+    G, gp = _f32(G)
+    d = G.shape[1]
+    rp, cp, vp = csr.ptrs()
+    b, bp = _u8(bits)
+    ww, wp = _f32(w)
+    mk, mp = _u8(mask)
+    streams = [np.zeros(code_bytes(d, int(bi)), dtype=np.uint8) for bi in b]
+    sp, keep = _stream_ptrs(streams)
+    sc_out = np.zeros((csr.n, num_buckets(d)), dtype=np.float32)
+    ghat = np.zeros(d, dtype=np.float32)
+    lib().agc_oracle_step_bucket(csr.n, d, gp, G.strides[0] // 4, rp, cp, vp, bp, wp, mp, int(seed),
+                                 int(step_), int(scale_mode), sp, sc_out.ctypes.data_as(_f32p),
+                                 ghat.ctypes.data_as(_f32p))
+    return streams, sc_out, ghat
 
 
 def threads():
