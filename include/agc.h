@@ -67,7 +67,10 @@ typedef struct {
     int scale_mode;    /* agc_scale_mode */
     int allow_1bit;    /* non-zero: accept b_i = 1 (two-point grid {-scale,+scale}; outside the paper, which needs b >= 2) */
     int force_generic; /* non-zero: never take the cyclic-band fast path (testing) */
-    int reserved[5];   /* must be zero */
+    int bucket;        /* 0: one scale per coded vector (the paper's quantizer).  256: one scale per
+                          256-coordinate bucket (Sec. II-B names the bucket-wise extension): the
+                          scales array becomes n x ceil(d/256) and the worker side reads G once */
+    int reserved[4];   /* must be zero */
 } agc_opts;
 
 /* --------------------------------------------------------------------------------------
@@ -96,6 +99,9 @@ int agc_code_path(const agc_ctx *ctx);
 /* Bytes of one worker's packed stream: ceil(d/128) * 16 * bits (Sec. II-B: the payload is
  * the scale plus d codes of b bits; the padding is this library's). */
 int64_t agc_code_bytes(int64_t d, int bits);
+
+/* Scales per worker in scales_dev: 1, or ceil(d/256) with bucket-wise scales. */
+int64_t agc_scales_per_worker(const agc_ctx *ctx);
 
 const char *agc_last_error(const agc_ctx *ctx);
 

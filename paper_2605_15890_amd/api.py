@@ -21,7 +21,7 @@ KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
-    "agc_decode2", "agc_adam_update", "agc_second_moment_decoder",
+    "agc_scales_per_worker", "agc_decode2", "agc_adam_update", "agc_second_moment_decoder",
     "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
@@ -30,7 +30,7 @@ EXPORTS = [
 
 class AgcOpts(C.Structure):
     _fields_ = [("scale_mode", C.c_int), ("allow_1bit", C.c_int), ("force_generic", C.c_int),
-                ("reserved", C.c_int * 5)]
+                ("bucket", C.c_int), ("reserved", C.c_int * 4)]
 
 
 class AgcError(RuntimeError):
@@ -78,6 +78,8 @@ def load():
     L.agc_encode_quantize.restype = C.c_int
     L.agc_decode.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _u8p, _vp, _vp]
     L.agc_decode.restype = C.c_int
+    L.agc_scales_per_worker.argtypes = [_vp]
+    L.agc_scales_per_worker.restype = C.c_int64
     L.agc_decode2.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _f32p, _u8p, _vp, _vp, _vp]
     L.agc_decode2.restype = C.c_int
     L.agc_adam_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, C.c_float, C.c_float,
@@ -232,10 +234,11 @@ def _stream_handle(stream):
 class Context:
     """Owns an agc_ctx and, for convenience, torch buffers for codes / scales / g_hat."""
 
-    def __init__(self, n, k, d, scale_mode=AGC_SCALE_MAXABS, allow_1bit=False, force_generic=False):
+    def __init__(self, n, k, d, scale_mode=AGC_SCALE_MAXABS, allow_1bit=False, force_generic=False, bucket=0):
         self.lib = load()
-        self.n, self.k, self.d = int(n), int(k), int(d)
-        opts = AgcOpts(int(scale_mode), int(bool(allow_1bit)), int(bool(force_generic)), (C.c_int * 5)())
+        self.n, self.k, self.d, self.bucket = int(n), int(k), int(d), int(bucket)
+        opts = AgcOpts(int(scale_mode), int(bool(allow_1bit)), int(bool(force_generic)), int(bucket),
+                       (C.c_int * 4)())
         h = _vp()
         st = self.lib.agc_create(C.byref(h), self.n, self.k, self.d, C.byref(opts))
         if st != AGC_OK:
@@ -264,12 +267,16 @@ class Context:
     def agc_code_path(self):
         return int(self.lib.agc_code_path(self.h))
 
+    def agc_scales_per_worker(self):
+        return int(self.lib.agc_scales_per_worker(self.h))
+
     # ---- buffers (torch: device memory only)
     def alloc_outputs(self, bits, device="cuda"):
         import torch
         bits = _np(bits, np.uint8)
         codes = [torch.empty(agc_code_bytes(self.d, int(b)), dtype=torch.uint8, device=device) for b in bits]
-        scales = torch.empty(self.n, dtype=torch.float32, device=device)
+        per = self.agc_scales_per_worker()
+        scales = torch.empty((self.n, per) if self.bucket else self.n, dtype=torch.float32, device=device)
         ghat = torch.empty(self.d, dtype=torch.float32, device=device)
         return codes, scales, ghat
 

@@ -160,6 +160,12 @@ int64_t agc_code_bytes(int64_t d, int bits)
     return ((d + 127) / 128) * 16 * (int64_t)bits;
 }
 
+int64_t agc_scales_per_worker(const agc_ctx* ctx)
+{
+    if (!ctx) return 0;
+    return ctx->opts.bucket ? (ctx->d + 255) / 256 : 1;
+}
+
 const char* agc_last_error(const agc_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
 agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* opts)
@@ -173,6 +179,7 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     if (opts) {
         o = *opts;
         if (o.scale_mode != AGC_SCALE_L2 && o.scale_mode != AGC_SCALE_MAXABS) return AGC_EINVAL;
+        if (o.bucket != 0 && o.bucket != 256) return AGC_EINVAL;
         for (int r : o.reserved)
             if (r != 0) return AGC_EINVAL;
     }
@@ -191,7 +198,9 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     c->ws.nseg = (nblocks + 3) / 4;
     c->ws.ngroup = (c->ws.nseg + 63) / 64;
     c->ws.nsuper = (c->ws.ngroup + 63) / 64;
-    if (o.scale_mode == AGC_SCALE_MAXABS) {
+    if (o.bucket) {
+        e = dev_alloc(&c->ws.srow, (size_t)n);  // the scales need no reduction workspace
+    } else if (o.scale_mode == AGC_SCALE_MAXABS) {
         e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nseg * n);
     } else {
         e = dev_alloc(&c->ws.part_sq, (size_t)c->ws.nseg * n);
@@ -221,6 +230,7 @@ void agc_destroy(agc_ctx* c)
     if (c->ws.wq) (void)hipFree(c->ws.wq);
     if (c->ws.wd) (void)hipFree(c->ws.wd);
     if (c->ws.coef2) (void)hipFree(c->ws.coef2);
+    if (c->ws.srow) (void)hipFree(c->ws.srow);
     for (auto& ring : c->events)
         for (auto& ep : ring) {
             if (ep.beg) (void)hipEventDestroy(ep.beg);
@@ -297,6 +307,14 @@ agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const ui
         qs.codes[i] = codes[i];
     }
     hipError_t e;
+    if (c->opts.bucket) {  // one pass: every block finds its own scale
+        KernelTimer t{c, 2, stream};
+        if ((st = t.begin()) != AGC_OK) return st;
+        e = agc::launch_quantize_bucket(G, ldg, c->n, c->k, c->d, code, c->opts.scale_mode, qs, c->ws, scales,
+                                        seed, step, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "bucket-wise quantize launch");
+        return t.end();
+    }
     {
         KernelTimer t{c, 0, stream};
         if ((st = t.begin()) != AGC_OK) return st;
@@ -342,7 +360,7 @@ agc_status agc_decode(agc_ctx* c, void* const* codes, const float* scales, const
     }
     KernelTimer t{c, 3, stream};
     if ((st = t.begin()) != AGC_OK) return st;
-    hipError_t e = agc::launch_decode(c->n, n_arrived, c->d, ds, scales, c->ws, ghat, stream);
+    hipError_t e = agc::launch_decode(c->n, n_arrived, c->d, ds, scales, c->opts.bucket ? (c->d + 255) / 256 : 0, c->ws, ghat, stream);
     if (e != hipSuccess) return hip_fail(c, e, "decode launch");
     return t.end();
 }
@@ -374,7 +392,7 @@ agc_status agc_decode2(agc_ctx* c, void* const* codes, const float* scales, cons
     }
     KernelTimer t{c, 3, stream};
     if ((st = t.begin()) != AGC_OK) return st;
-    hipError_t e = agc::launch_decode2(c->n, n_arrived, c->d, ds, d2, scales, c->ws, ghat, ghat2, stream);
+    hipError_t e = agc::launch_decode2(c->n, n_arrived, c->d, ds, d2, scales, c->opts.bucket ? (c->d + 255) / 256 : 0, c->ws, ghat, ghat2, stream);
     if (e != hipSuccess) return hip_fail(c, e, "two-track decode launch");
     return t.end();
 }

@@ -39,6 +39,7 @@ struct Workspace {
     WorkerQ* wq;          // [n]  written by the scale finalize
     WorkerD* wd;          // [n]  arrived workers, compacted, written by the decode prologue
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
+    const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker
     int64_t nseg, ngroup, nsuper;
 };
 
@@ -71,13 +72,20 @@ hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
                            hipStream_t stream);
+// Bucket-wise scales (one per 256-coordinate block and worker): a table prologue, then ONE pass
+// over G that derives each block's scale from the block itself.  scales: n x nb, nb = ceil(d/256).
+hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,
+                                  int scale_mode, const QuantStreams& out, const Workspace& ws, float* scales,
+                                  uint64_t seed, uint64_t step, hipStream_t stream);
 // K3: table of the arrived workers (a one-workgroup prologue), then masked dequantize +
 // weighted sum.
+// nb = 0: one scale per worker; nb > 0: scales is n x nb, one scale per 256-coordinate bucket.
 hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
-                         const float* scales, const Workspace& ws, float* ghat, hipStream_t stream);
+                         const float* scales, int64_t nb, const Workspace& ws, float* ghat,
+                         hipStream_t stream);
 // Two-track variant: the same read of the codes feeds a second weighted sum with weights v.
 hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& in, const DecodeSecond& second,
-                          const float* scales, const Workspace& ws, float* ghat, float* ghat2,
+                          const float* scales, int64_t nb, const Workspace& ws, float* ghat, float* ghat2,
                           hipStream_t stream);
 // Adam update that takes its first moment from ghat and its second moment from ghat2.
 hipError_t launch_adam_update(float* beta, float* m1, float* m2, const float* ghat, const float* ghat2,

@@ -242,6 +242,8 @@ struct QuantArgs {
     int n, k;
     int64_t d;
     uint32_t key0, key1, step_lo, step_hi;
+    float* scales;  // bucket-wise scales only: n x nb
+    int64_t nb;
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
@@ -285,6 +287,11 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// BUCKET 0: the worker's multiplier comes from the table (one scale per vector).
+// BUCKET 1 / 2: one scale per 256-coordinate block, derived here from the block itself (largest
+// magnitude / Euclidean norm), stored by lane 0, and turned into the multiplier with one binary32
+// division (Sec. II-B names the bucket-wise extension; this is its single-pass form).
+template <int BUCKET>
 struct EpiQuant {
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
@@ -296,6 +303,26 @@ struct EpiQuant {
     int nvalid;
     bool wave_ragged;    // wave-uniform: some lane has coordinates >= d
     uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
+    float* scales;          // bucket-wise scales: n x nb
+    int64_t nb;
+
+    __device__ __forceinline__ float block_multiplier(int i, const float4& f, int b)
+    {
+        float scale;
+        if (BUCKET == 1) {
+            const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+            scale = __uint_as_float(wave_max_nonneg_bits(a));
+        } else {
+            const double x0 = f.x, x1 = f.y, x2 = f.z, x3 = f.w;
+            const double s01 = x0 * x0 + x1 * x1;
+            const double s23 = x2 * x2 + x3 * x3;
+            scale = (float)sqrt(wave_butterfly_add(s01 + s23));
+        }
+        if (lane == 0) *((__attribute__((address_space(1))) float*)scales + ((int64_t)i * nb + block)) = scale;
+        const float num = b >= 2 ? (float)(((1u << (b - 1)) - 1u) << 16) : 32768.0f;
+        const float q = num / scale;  // correctly rounded binary32 division
+        return (scale > 0.0f && q <= 3.402823466e+38f) ? q : 0.0f;
+    }
 
     // four rounding decisions; only the grid position differs between the regular grid
     // (b >= 2) and the two-point grid of a one-bit worker
@@ -351,7 +378,8 @@ struct EpiQuant {
         const WorkerQ q = wq[i];  // wave-uniform: one scalar 16-byte load
         const int b = (int)q.bits;
         uint32_t c[4];
-        codes4(i, f, q.inv16, b, wa, wb, c);
+        const float inv = BUCKET == 0 ? q.inv16 : block_multiplier(i, f, b);
+        codes4(i, f, inv, b, wa, wb, c);
 
         // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
         const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
@@ -391,7 +419,7 @@ struct EpiQuant {
     }
 };
 
-template <int S>
+template <int S, int BUCKET>
 __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
@@ -408,39 +436,68 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
     if (base >= a.d) return;
     const LaneCoords lc = lane_coords(base, lane, a.d);
     const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
-    EpiQuant epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
-                 groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
-                 lc.wave_ragged, 0u, 0u};
+    EpiQuant<BUCKET> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
+                         groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
+                         lc.wave_ragged, 0u, 0u, a.scales, a.nb};
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
 }
 
-template <int S>
+template <int S, int BUCKET>
 static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const WorkerQ* wq,
                                     const QuantArgs& a, hipStream_t stream)
 {
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
-    hipLaunchKernelGGL((k_quantize<S>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr, code.col,
-                       code.val, wq, a);
+    hipLaunchKernelGGL((k_quantize<S, BUCKET>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                       code.col, code.val, wq, a);
     return hipGetLastError();
+}
+
+template <int BUCKET>
+static hipError_t launch_quantize_band(const float* G, const CodeDev& code, const WorkerQ* wq,
+                                       const QuantArgs& a, hipStream_t stream)
+{
+    switch (code.band) {
+        case 1: return launch_quantize_s<1, BUCKET>(G, code, wq, a, stream);
+        case 2: return launch_quantize_s<2, BUCKET>(G, code, wq, a, stream);
+        case 3: return launch_quantize_s<3, BUCKET>(G, code, wq, a, stream);
+        case 4: return launch_quantize_s<4, BUCKET>(G, code, wq, a, stream);
+        case 5: return launch_quantize_s<5, BUCKET>(G, code, wq, a, stream);
+        case 6: return launch_quantize_s<6, BUCKET>(G, code, wq, a, stream);
+        case 7: return launch_quantize_s<7, BUCKET>(G, code, wq, a, stream);
+        case 8: return launch_quantize_s<8, BUCKET>(G, code, wq, a, stream);
+        default: return launch_quantize_s<0, BUCKET>(G, code, wq, a, stream);
+    }
+}
+
+// table of the bucket-wise pass: bit-width and stream of every worker (the multiplier is
+// found per block inside the pass)
+__global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams out, WorkerQ* wq)
+{
+    const int i = threadIdx.x;
+    if (i < n) wq[i] = WorkerQ{0.0f, (uint32_t)out.bits[i], out.codes[i]};
+}
+
+hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,
+                                  int scale_mode, const QuantStreams& out, const Workspace& ws, float* scales,
+                                  uint64_t seed, uint64_t step, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_quant_table, dim3(1), dim3(kWgThreads), 0, stream, n, out, ws.wq);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
+                scales, (d + kBlockCoords - 1) / kBlockCoords};
+    return scale_mode == 0 ? launch_quantize_band<2>(G, code, ws.wq, a, stream)
+                           : launch_quantize_band<1>(G, code, ws.wq, a, stream);
 }
 
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
                            hipStream_t stream)
 {
-    QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
-    switch (code.band) {
-        case 1: return launch_quantize_s<1>(G, code, ws.wq, a, stream);
-        case 2: return launch_quantize_s<2>(G, code, ws.wq, a, stream);
-        case 3: return launch_quantize_s<3>(G, code, ws.wq, a, stream);
-        case 4: return launch_quantize_s<4>(G, code, ws.wq, a, stream);
-        case 5: return launch_quantize_s<5>(G, code, ws.wq, a, stream);
-        case 6: return launch_quantize_s<6>(G, code, ws.wq, a, stream);
-        case 7: return launch_quantize_s<7>(G, code, ws.wq, a, stream);
-        case 8: return launch_quantize_s<8>(G, code, ws.wq, a, stream);
-        default: return launch_quantize_s<0>(G, code, ws.wq, a, stream);
-    }
+    QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
+                nullptr, 0};
+    return launch_quantize_band<0>(G, code, ws.wq, a, stream);
 }
 
 // =======================================================================================
@@ -452,8 +509,11 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
 constexpr int kDecCoords = 32;
 
 // prologue: one entry per ARRIVED worker, in ascending worker order
+// nb == 0: one scale per worker, folded into the weight here.  nb > 0: bucket-wise scales; the
+// table holds w_i / L_i and the worker's row of scales, the product is formed per bucket.
 __global__ __launch_bounds__(kWgThreads) void k_decode_table(int n, DecodeStreams in,
-                                                             const float* scales, WorkerD* wd)
+                                                             const float* scales, int64_t nb, WorkerD* wd,
+                                                             const float** srow)
 {
     const int i = threadIdx.x;
     if (i >= n) return;
@@ -462,13 +522,18 @@ __global__ __launch_bounds__(kWgThreads) void k_decode_table(int n, DecodeStream
     const int b = in.bits[i];
     // weight of one grid unit of worker i: w_i * scale_i / L_i, binary64 then one rounding
     const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
-    wd[slot] = WorkerD{in.codes[i], (float)(((double)in.w[i] * (double)scales[i]) / L), (uint32_t)b};
+    if (nb == 0) {
+        wd[slot] = WorkerD{in.codes[i], (float)(((double)in.w[i] * (double)scales[i]) / L), (uint32_t)b};
+    } else {
+        wd[slot] = WorkerD{in.codes[i], (float)((double)in.w[i] / L), (uint32_t)b};
+        srow[slot] = scales + (int64_t)i * nb;
+    }
 }
 
 // second table of the two-track decode: weight of one grid unit of worker i under the
 // second decoding vector, v_i * scale_i / L_i, same rounding as the first
 __global__ __launch_bounds__(kWgThreads) void k_decode_table2(int n, DecodeSecond in, const float* scales,
-                                                              float* coef2)
+                                                              int64_t nb, float* coef2)
 {
     const int i = threadIdx.x;
     if (i >= n) return;
@@ -476,7 +541,7 @@ __global__ __launch_bounds__(kWgThreads) void k_decode_table2(int n, DecodeSecon
     if (slot == 0xFFFFu) return;
     const int b = in.bits[i];
     const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
-    coef2[slot] = (float)(((double)in.v[i] * (double)scales[i]) / L);
+    coef2[slot] = nb == 0 ? (float)(((double)in.v[i] * (double)scales[i]) / L) : (float)((double)in.v[i] / L);
 }
 
 template <int B, bool TWO>
@@ -530,9 +595,10 @@ __device__ __forceinline__ void store_coords(float* dst, const float (&acc)[kDec
     }
 }
 
-template <bool TWO>
+template <bool TWO, bool BUCKET>
 __global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict__ wd,
-                                                       const float* __restrict__ coef2, DecodeArgs a)
+                                                       const float* __restrict__ coef2,
+                                                       const float* const* __restrict__ srow, DecodeArgs a)
 {
     const int64_t t = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
     const int64_t m0 = t * kDecCoords;
@@ -545,61 +611,79 @@ __global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict
     for (int q = 0; q < (TWO ? kDecCoords : 1); ++q) acc2[q] = 0.f;
     for (int e = 0; e < a.n_arrived; ++e) {
         const WorkerD wk = wd[e];  // wave-uniform: one scalar 16-byte load
-        const float c2 = TWO ? coef2[e] : 0.f;
+        float c1 = wk.coef;
+        float c2 = TWO ? coef2[e] : 0.f;
+        if (BUCKET) {  // the lane's 32 coordinates lie in one 256-coordinate bucket
+            const float sc = ((const __attribute__((address_space(1))) float*)srow[e])[t >> 3];
+            c1 = c1 * sc;
+            c2 = c2 * sc;
+        }
         const int b = (int)wk.bits;
         const global_u32* src = (const global_u32*)wk.codes + t * b;
         switch (b) {
-            case 1: decode_words<1, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 2: decode_words<2, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 3: decode_words<3, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 4: decode_words<4, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 5: decode_words<5, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 6: decode_words<6, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 7: decode_words<7, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 8: decode_words<8, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 9: decode_words<9, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 10: decode_words<10, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 11: decode_words<11, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 12: decode_words<12, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 13: decode_words<13, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 14: decode_words<14, TWO>(src, wk.coef, c2, acc, acc2); break;
-            case 15: decode_words<15, TWO>(src, wk.coef, c2, acc, acc2); break;
-            default: decode_words<16, TWO>(src, wk.coef, c2, acc, acc2); break;
+            case 1: decode_words<1, TWO>(src, c1, c2, acc, acc2); break;
+            case 2: decode_words<2, TWO>(src, c1, c2, acc, acc2); break;
+            case 3: decode_words<3, TWO>(src, c1, c2, acc, acc2); break;
+            case 4: decode_words<4, TWO>(src, c1, c2, acc, acc2); break;
+            case 5: decode_words<5, TWO>(src, c1, c2, acc, acc2); break;
+            case 6: decode_words<6, TWO>(src, c1, c2, acc, acc2); break;
+            case 7: decode_words<7, TWO>(src, c1, c2, acc, acc2); break;
+            case 8: decode_words<8, TWO>(src, c1, c2, acc, acc2); break;
+            case 9: decode_words<9, TWO>(src, c1, c2, acc, acc2); break;
+            case 10: decode_words<10, TWO>(src, c1, c2, acc, acc2); break;
+            case 11: decode_words<11, TWO>(src, c1, c2, acc, acc2); break;
+            case 12: decode_words<12, TWO>(src, c1, c2, acc, acc2); break;
+            case 13: decode_words<13, TWO>(src, c1, c2, acc, acc2); break;
+            case 14: decode_words<14, TWO>(src, c1, c2, acc, acc2); break;
+            case 15: decode_words<15, TWO>(src, c1, c2, acc, acc2); break;
+            default: decode_words<16, TWO>(src, c1, c2, acc, acc2); break;
         }
     }
     store_coords(a.ghat + m0, acc, m0, a.d);
     if constexpr (TWO) store_coords(a.ghat2 + m0, acc2, m0, a.d);
 }
 
-hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
-                         const float* scales, const Workspace& ws, float* ghat, hipStream_t stream)
+template <bool TWO>
+static void launch_decode_kernel(bool bucket, unsigned grid, hipStream_t stream, const Workspace& ws,
+                                 const DecodeArgs& a)
 {
-    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, ws.wd);
+    const float* c2 = TWO ? ws.coef2 : nullptr;
+    if (bucket)
+        hipLaunchKernelGGL((k_decode<TWO, true>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
+                           (const float* const*)ws.srow, a);
+    else
+        hipLaunchKernelGGL((k_decode<TWO, false>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
+                           (const float* const*)nullptr, a);
+}
+
+hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
+                         const float* scales, int64_t nb, const Workspace& ws, float* ghat,
+                         hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     DecodeArgs a{n_arrived, d, ghat, nullptr};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    hipLaunchKernelGGL(k_decode<false>, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd,
-                       static_cast<const float*>(nullptr), a);
+    launch_decode_kernel<false>(nb > 0, grid, stream, ws, a);
     return hipGetLastError();
 }
 
 hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& in, const DecodeSecond& second,
-                          const float* scales, const Workspace& ws, float* ghat, float* ghat2,
+                          const float* scales, int64_t nb, const Workspace& ws, float* ghat, float* ghat2,
                           hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, ws.wd);
+    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_decode_table2, dim3(1), dim3(kWgThreads), 0, stream, n, second, scales, ws.coef2);
+    hipLaunchKernelGGL(k_decode_table2, dim3(1), dim3(kWgThreads), 0, stream, n, second, scales, nb, ws.coef2);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     DecodeArgs a{n_arrived, d, ghat, ghat2};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    hipLaunchKernelGGL(k_decode<true>, dim3(grid), dim3(kWgThreads), 0, stream, ws.wd,
-                       static_cast<const float*>(ws.coef2), a);
+    launch_decode_kernel<true>(nb > 0, grid, stream, ws, a);
     return hipGetLastError();
 }
 
