@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--scale", default="maxabs", choices=["maxabs", "l2"])
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
+    ap.add_argument("--bucket", type=int, default=0, choices=[0, 256],
+                    help="256: one scale per 256-coordinate bucket (single pass over G); 0: one per vector")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=23,
                     help="the oracle is timed on the first 2^this coordinates (all partitions)")
@@ -170,9 +172,10 @@ def main():
 
     G = I.partial_gradients_torch(cfg, dev)
     assert G.stride(0) % 4 == 0 and G.data_ptr() % 16 == 0
-    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit)
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=args.bucket)
     ctx.agc_set_code(*code)
     codes, scales, ghat = ctx.alloc_outputs(bits)
+    nb = ctx.agc_scales_per_worker() if args.bucket else 0
     K, W = args.steps, args.warmup
     masks = [I.arrival_mask(cfg, p, t) for t in range(W + K)]     # sampled outside the timed region
     seed = cfg.philox_seed
@@ -203,14 +206,17 @@ def main():
     # algorithmic bytes per launch of each kernel (what the method must move)
     sum_b = float(np.sum(bits))
     arrived_b = float(np.mean([np.sum(bits[m.astype(bool)]) for m in masks[W:]]))
+    n_arr = float(np.mean([m.sum() for m in masks[W:]]))
     alg_bytes = {
-        "scale_pass": 4.0 * k * d,
+        "scale_pass": 0.0 if args.bucket else 4.0 * k * d,
         "scale_finalize": 0.0,
-        "quantize": 4.0 * k * d + d * sum_b / 8.0,
-        "decode": d * arrived_b / 8.0 + 4.0 * d,
+        "quantize": 4.0 * k * d + d * sum_b / 8.0 + 4.0 * n * nb,
+        "decode": d * arrived_b / 8.0 + 4.0 * d + 4.0 * n_arr * nb,
     }
     kernels = {}
     for name, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
         avg = ms / max(cnt, 1)
         kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
                          "alg_GBps": round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1) if avg > 0 else None}
@@ -218,7 +224,8 @@ def main():
     dom_avg_s = kernels[dominant]["avg_ms"] * 1e-3
     achieved = alg_bytes[dominant] / dom_avg_s / 1e9
     step_alg_bytes = sum(alg_bytes.values())
-    traffic, traffic_src = stored_traffic(f"{cfg.name}_{args.code}_{args.scale}", dominant)
+    tag = f"{cfg.name}_{args.code}_{args.scale}" + (f"_bucket{args.bucket}" if args.bucket else "")
+    traffic, traffic_src = stored_traffic(tag, dominant)
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -236,7 +243,8 @@ def main():
         Gs = G[:, :ds].contiguous().cpu().numpy()
         csr = O.Csr(code[0], code[1], code[2], k)
         c0 = time.perf_counter()
-        O.step(Gs, csr, bits, w, masks[W], seed, W, O.SCALE_MAXABS if args.scale == "maxabs" else O.SCALE_L2)
+        o_mode = O.SCALE_MAXABS if args.scale == "maxabs" else O.SCALE_L2
+        (O.step_bucket if args.bucket else O.step)(Gs, csr, bits, w, masks[W], seed, W, o_mode)
         c1 = time.perf_counter()
         cpu_baseline = {
             "value": round(4.0 * k * ds / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": O.threads(),
@@ -252,7 +260,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} workers, k={k} partitions, s={cfg.s}, d={d}, "
                                f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
-                               f"{args.code} code, {args.scale} scale",
+                               f"{args.code} code, {args.scale} scale"
+                               + (f" per {args.bucket}-coordinate bucket" if args.bucket else " per vector"),
                    "code_path": ctx.agc_code_path()},
         "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
