@@ -263,6 +263,16 @@ agc_status agc_build_code(int n, int k, const double *p, const uint8_t *bits, do
 agc_status agc_build_cyclic_code(int n, int k, int s, const double *p, const uint8_t *bits,
                                  double phi_coef, int32_t *row_ptr, int32_t *col, float *val,
                                  float *w_out);
+/* Optimum of the structure problem (Sec. III-A, problem c-SP2) restricted to the same cyclic
+ * support: minimises sum_i c_i (sum_j alpha_i^j)^2 over alpha >= 0 with column sums 1, by exact
+ * minimisation over one column at a time (convex, converges to the optimum).  When the support
+ * admits the row sums of Theorem 1 the result has them and *objective equals k^2 / sum_i c_i^-1
+ * (then *reaches_bound = 1); otherwise it is the best the support allows.  A worker may end with
+ * zero weight on a partition it holds (the entry is kept, with value 0, so that the layout stays
+ * cyclic).  Outputs as agc_build_cyclic_code; objective and reaches_bound may be NULL. */
+agc_status agc_build_cyclic_code_opt(int n, int k, int s, const double *p, const uint8_t *bits,
+                                     double phi_coef, int32_t *row_ptr, int32_t *col, float *val,
+                                     float *w_out, double *objective, int *reaches_bound);
 /* Unbiasedness condition of Sec. III: max_j | sum_i (1-p_i) w_i a_ij - 1 | <= tol (binary64
  * over the binary32 inputs).  AGC_OK when it holds, AGC_EINVAL when it does not;
  * *residual (may be NULL) receives the maximum. */

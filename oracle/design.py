@@ -254,6 +254,64 @@ def cyclic_code(c, k, s):
     return alpha, supp
 
 
+def cyclic_row_sum_feasible(c, k, s):
+    """Is Theorem 1's structure reachable on the cyclic support?  Linear feasibility of
+    alpha >= 0 on the support with row sums Y_i and column sums 1 (a transportation problem),
+    decided with a library LP solver.  Returns (feasible, alpha or None)."""
+    from scipy.optimize import linprog
+    n = len(c)
+    supp = cyclic_support(n, k, s)
+    Y = row_targets(c, k)
+    nv = n * s
+    A_eq = np.zeros((n + k, nv))
+    b_eq = np.concatenate([Y, np.ones(k)])
+    for i in range(n):
+        for u, j in enumerate(supp[i]):
+            A_eq[i, i * s + u] = 1.0
+            A_eq[n + j, i * s + u] = 1.0
+    res = linprog(np.zeros(nv), A_eq=A_eq, b_eq=b_eq, bounds=[(0, None)] * nv, method="highs")
+    if res.status != 0:
+        return False, None
+    alpha = np.zeros((n, k))
+    for i in range(n):
+        for u, j in enumerate(supp[i]):
+            alpha[i, j] = res.x[i * s + u]
+    return True, alpha
+
+
+def cyclic_code_optimal(c, k, s):
+    """Problem c-SP2 restricted to the cyclic support: minimise sum_i c_i (sum_j alpha_i^j)^2
+    subject to column sums 1, alpha >= 0, alpha = 0 off the support.  The objective depends on
+    the row sums only, so it is a convex quadratic programme in them; solved here with a
+    library routine (SLSQP from the column-normalised start, analytic gradient).  When the row
+    sums of Theorem 1 are reachable the minimum is k^2 / sum c^-1."""
+    from scipy.optimize import minimize
+    c = np.asarray(c, dtype=np.float64)
+    n = len(c)
+    supp = cyclic_support(n, k, s)
+    a0, _ = cyclic_code(c, k, s)
+    x0 = np.array([a0[i, j] for i in range(n) for j in supp[i]])
+    cols = np.array([j for i in range(n) for j in supp[i]])
+    rows = np.repeat(np.arange(n), s)
+
+    def f(x):
+        r = np.bincount(rows, weights=x, minlength=n)
+        return float(np.sum(c * r * r))
+
+    def g(x):
+        r = np.bincount(rows, weights=x, minlength=n)
+        return 2.0 * (c * r)[rows]
+
+    Ac = np.zeros((k, n * s))
+    Ac[cols, np.arange(n * s)] = 1.0
+    res = minimize(f, x0, jac=g, method="SLSQP", bounds=[(0.0, None)] * (n * s),
+                   constraints=[{"type": "eq", "fun": lambda x: Ac @ x - 1.0, "jac": lambda x: Ac}],
+                   options={"ftol": 1e-15, "maxiter": 2000})
+    alpha = np.zeros((n, k))
+    alpha[rows, cols] = np.maximum(res.x, 0.0)
+    return alpha, supp
+
+
 def physical_code(alpha, p):
     """a_ij = alpha_i^j / w~_i, w_i = w~_i / (1 - p_i) with the free w~_i := 1."""
     p = np.asarray(p, dtype=np.float64)

@@ -24,7 +24,7 @@ EXPORTS = [
     "agc_scales_per_worker", "agc_decode2", "agc_adam_update", "agc_second_moment_decoder",
     "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
-    "agc_build_code", "agc_build_cyclic_code", "agc_check_unbiased",
+    "agc_build_code", "agc_build_cyclic_code", "agc_build_cyclic_code_opt", "agc_check_unbiased",
 ]
 
 
@@ -118,6 +118,9 @@ def load():
     L.agc_build_cyclic_code.argtypes = [C.c_int, C.c_int, C.c_int, _f64p, _u8p, C.c_double, _i32p,
                                         _i32p, _f32p, _f32p]
     L.agc_build_cyclic_code.restype = C.c_int
+    L.agc_build_cyclic_code_opt.argtypes = [C.c_int, C.c_int, C.c_int, _f64p, _u8p, C.c_double, _i32p,
+                                            _i32p, _f32p, _f32p, _f64p, C.POINTER(C.c_int)]
+    L.agc_build_cyclic_code_opt.restype = C.c_int
     L.agc_check_unbiased.argtypes = [C.c_int, C.c_int, _i32p, _i32p, _f32p, _f32p, _f64p,
                                      C.c_double, _f64p]
     L.agc_check_unbiased.restype = C.c_int
@@ -195,6 +198,23 @@ def agc_build_cyclic_code(n, k, s, p, bits, phi_coef):
     if st != AGC_OK:
         raise AgcError(st, "agc_build_cyclic_code")
     return row_ptr, col, val, w
+
+
+def agc_build_cyclic_code_opt(n, k, s, p, bits, phi_coef):
+    """Optimal weights on the cyclic support.  Returns (row_ptr, col, val, w, objective, reaches_bound)."""
+    p = _np(p, np.float64)
+    bits = _np(bits, np.uint8)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    col = np.zeros(n * s, dtype=np.int32)
+    val = np.zeros(n * s, dtype=np.float32)
+    w = np.zeros(n, dtype=np.float32)
+    obj, reach = C.c_double(), C.c_int()
+    st = load().agc_build_cyclic_code_opt(n, k, s, _ptr(p, _f64p), _ptr(bits, _u8p), float(phi_coef),
+                                          _ptr(row_ptr, _i32p), _ptr(col, _i32p), _ptr(val, _f32p), _ptr(w, _f32p),
+                                          C.byref(obj), C.byref(reach))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_build_cyclic_code_opt")
+    return row_ptr, col, val, w, float(obj.value), bool(reach.value)
 
 
 def agc_check_unbiased(k, row_ptr, col, val, w, p, tol=1e-5):

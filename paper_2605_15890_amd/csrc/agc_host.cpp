@@ -298,6 +298,91 @@ agc_status agc_build_cyclic_code(int n, int k, int s, const double* p, const uin
     return AGC_OK;
 }
 
+// Problem c-SP2 on the cyclic support {i, .., i+s-1 mod k} (n == k):  minimise
+// sum_i c_i r_i^2, r_i = sum_j alpha_i^j, subject to column sums 1 and alpha >= 0.  The objective
+// is convex and its constraints are one simplex per column, so exact minimisation over one column
+// at a time converges to the optimum.  One column step: with a_i the row sums without this
+// column's entries, the unit mass goes to the holders in order of increasing marginal cost
+// 2 c_i a_i until they share one level mu (x_i = max(0, mu / (2 c_i) - a_i), sum x_i = 1).
+agc_status agc_build_cyclic_code_opt(int n, int k, int s, const double* p, const uint8_t* bits,
+                                     double phi_coef, int32_t* row_ptr, int32_t* col, float* val,
+                                     float* w_out, double* objective, int* reaches_bound)
+{
+    if (!p || !bits || !row_ptr || !col || !val || !w_out) return AGC_EINVAL;
+    if (n <= 0 || k <= 0 || n != k || s < 1 || s > k) return AGC_ESHAPE;
+    std::vector<double> cinv;
+    agc_status st = code_weights(n, p, bits, phi_coef, cinv);
+    if (st != AGC_OK) return st;
+    // start from the column-normalised weights
+    std::vector<double> alpha((size_t)n * s), r(n, 0.0), colsum(k, 0.0);
+    for (int i = 0; i < n; ++i)
+        for (int u = 0; u < s; ++u) colsum[(i + u) % k] += cinv[i];
+    for (int i = 0; i < n; ++i)
+        for (int u = 0; u < s; ++u) {
+            alpha[(size_t)i * s + u] = cinv[i] / colsum[(i + u) % k];
+            r[i] += alpha[(size_t)i * s + u];
+        }
+    std::vector<int> order(s);
+    std::vector<double> a(s), x(s);
+    const int max_sweeps = 200000;
+    for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+        double moved = 0.0;
+        for (int j = 0; j < k; ++j) {
+            // holders of column j: worker (j - u) mod n holds it at position u
+            for (int u = 0; u < s; ++u) {
+                const int i = ((j - u) % n + n) % n;
+                a[u] = r[i] - alpha[(size_t)i * s + u];
+                order[u] = u;
+            }
+            std::sort(order.begin(), order.end(), [&](int u1, int u2) {
+                const int i1 = ((j - u1) % n + n) % n, i2 = ((j - u2) % n + n) % n;
+                return a[u1] / cinv[i1] < a[u2] / cinv[i2];  // marginal cost c_i a_i
+            });
+            // level mu/2 = (1 + sum_{active} a_i) / sum_{active} c_i^-1 over the cheapest m holders
+            double sum_a = 0.0, sum_cinv = 0.0, level = 0.0;
+            int m = 0;
+            for (; m < s; ++m) {
+                const int u = order[m], i = ((j - u) % n + n) % n;
+                if (m > 0 && a[u] / cinv[i] >= level) break;  // this holder is already above the level
+                sum_a += a[u];
+                sum_cinv += cinv[i];
+                level = (1.0 + sum_a) / sum_cinv;
+            }
+            for (int u = 0; u < s; ++u) x[u] = 0.0;
+            for (int q = 0; q < m; ++q) {
+                const int u = order[q], i = ((j - u) % n + n) % n;
+                x[u] = std::max(0.0, level * cinv[i] - a[u]);
+            }
+            double tot = 0.0;
+            for (int u = 0; u < s; ++u) tot += x[u];
+            for (int u = 0; u < s; ++u) {
+                const int i = ((j - u) % n + n) % n;
+                const double nx = x[u] / tot;  // rounding left the sum a few ulps off 1
+                moved = std::max(moved, std::fabs(nx - alpha[(size_t)i * s + u]));
+                alpha[(size_t)i * s + u] = nx;
+                r[i] = a[u] + nx;
+            }
+        }
+        if (moved < 1e-15) break;
+    }
+    double obj = 0.0, inv_sum = 0.0;
+    for (int i = 0; i < n; ++i) {
+        obj += r[i] * r[i] / cinv[i];
+        inv_sum += cinv[i];
+        row_ptr[i] = i * s;
+        for (int u = 0; u < s; ++u) {
+            col[i * s + u] = (i + u) % k;
+            val[i * s + u] = (float)alpha[(size_t)i * s + u];
+        }
+        w_out[i] = (float)(1.0 / (1.0 - p[i]));
+    }
+    row_ptr[n] = n * s;
+    if (objective) *objective = obj;
+    // Theorem 1's row sums are reachable on this support iff the minimum equals k^2 / sum c^-1
+    if (reaches_bound) *reaches_bound = obj <= (double)k * k / inv_sum * (1.0 + 1e-9) ? 1 : 0;
+    return AGC_OK;
+}
+
 agc_status agc_check_unbiased(int n, int k, const int32_t* row_ptr, const int32_t* col,
                               const float* val, const float* w, const double* p, double tol,
                               double* residual)

@@ -256,3 +256,24 @@ def test_montecarlo_unbiased_on_gpu():
     z = proj.mean(axis=0) / (proj.std(axis=0, ddof=1) / np.sqrt(T))
     assert np.all(np.abs(z) < 3.0), z
     ctx.close()
+
+
+def test_optimal_cyclic_code_runs_on_the_band_path():
+    """Weights from the support-restricted optimum (some stored entries are exactly zero): the
+    layout is still cyclic, so the register-ring path must take it, with the oracle's bits."""
+    cfg = I.CONFIGS["n16_d1m"]
+    d = (1 << 16) + 77
+    p = I.straggler_probs(cfg)
+    z_tot = cfg.bits_law[1] * cfg.n
+    bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    row_ptr, col, val, w, obj, reach = api.agc_build_cyclic_code_opt(cfg.n, cfg.k, cfg.s, p, bits, pc)
+    assert (val == 0).any()
+    G = I.partial_gradients_numpy(cfg, d=d)
+    Gd = to_device(G)
+    for scale_mode in MODES:
+        mask = I.arrival_mask(cfg, p, 1)
+        out = run_hip(Gd, cfg.n, cfg.k, d, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 1, scale_mode,
+                      expect_path=cfg.s)
+        compare_with_oracle(G, cfg.k, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 1, scale_mode, out,
+                            tag=f"optimal cyclic mode={scale_mode}")

@@ -165,3 +165,40 @@ def test_second_moment_decoder_matches_oracle_and_beats_unbiased_decoder():
             assert var(v.astype(np.float64)) <= var(w.astype(np.float64)) * (1 + 1e-6)
     with pytest.raises(api.AgcError):
         api.agc_second_moment_decoder(4, [0, 1, 2, 3, 4], [0, 1, 2, 3], [1, 1, 1, 1], [0.1] * 4, [4] * 4, 0.2, 0.0)
+
+
+def test_optimal_cyclic_code_matches_the_oracle_optimum():
+    """Support-restricted structure problem: the library's column-wise minimisation against the
+    oracle's library solver (objective), Theorem 1's value when the support admits it, and the
+    unbiasedness condition; never worse than the column-normalised heuristic."""
+    rng = np.random.default_rng(41)
+    saw_bound, saw_gap = False, False
+    for n, s in [(6, 6), (10, 2), (10, 3), (16, 3), (12, 1), (24, 4)]:
+        p = rng.uniform(0.02, 0.7, n)
+        bits = rng.integers(2, 9, n).astype(np.uint8)
+        c = D.c_weights(p, bits, 0.3)
+        row_ptr, col, val, w, obj, reach = api.agc_build_cyclic_code_opt(n, n, s, p, bits, 0.3)
+        assert np.array_equal(row_ptr, np.arange(n + 1) * s)
+        assert np.array_equal(col.reshape(n, s), np.array(D.cyclic_support(n, n, s)))
+        ok, res = api.agc_check_unbiased(n, row_ptr, col, val, w, p, 1e-5)
+        assert ok, res
+        a_o, _ = D.cyclic_code_optimal(c, n, s)
+        obj_o = D.csp2_objective(c, a_o)
+        assert obj <= obj_o * (1 + 1e-7), (n, s, obj, obj_o)           # at least as good as the library solver
+        assert obj >= n * n / np.sum(1 / c) * (1 - 1e-12)              # and never below Theorem 1's value
+        alpha = np.zeros((n, n))
+        for i in range(n):
+            alpha[i, col[row_ptr[i]:row_ptr[i + 1]]] = val[row_ptr[i]:row_ptr[i + 1]]
+        assert abs(D.csp2_objective(c, alpha) - obj) <= 1e-5 * obj     # the float32 entries carry that objective
+        heur = D.csp2_objective(c, D.cyclic_code(c, n, s)[0])
+        assert obj <= heur * (1 + 1e-12)
+        feasible, _ = D.cyclic_row_sum_feasible(c, n, s)
+        assert reach == feasible
+        if reach:
+            saw_bound = True
+            assert np.allclose(alpha.sum(axis=1), D.row_targets(c, n), rtol=1e-5)
+        else:
+            saw_gap = True
+    assert saw_bound and saw_gap
+    with pytest.raises(api.AgcError):
+        api.agc_build_cyclic_code_opt(4, 5, 2, [0.1] * 4, [2] * 4, 0.2)

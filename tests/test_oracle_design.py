@@ -182,3 +182,69 @@ def test_second_moment_decoder_minimises_objective():
         assert m0 <= D.second_moment_objective(w, p, z, 0.4, B, Lam)      # beats the unbiased decoder
         for _ in range(20):
             assert m0 <= D.second_moment_objective(v + 1e-3 * rng.standard_normal(n), p, z, 0.4, B, Lam)
+
+
+# ------------------------------------------------------------------ optimum on a prescribed cyclic support
+def _kkt_gap(c, alpha, supp, k):
+    """Optimality conditions of the support-restricted problem: inside every column the
+    holders that carry weight share the smallest marginal cost 2 c_i r_i."""
+    r = alpha.sum(axis=1)
+    worst = 0.0
+    for j in range(k):
+        holders = [i for i in range(len(c)) if j in supp[i]]
+        m = np.array([2 * c[i] * r[i] for i in holders])
+        a = np.array([alpha[i, j] for i in holders])
+        lo = m.min()
+        worst = max(worst, float(np.max((m - lo) * (a > 1e-7)) / max(lo, 1e-300)))
+    return worst
+
+
+def test_cyclic_optimum_full_support_reaches_theorem_1():
+    rng = np.random.default_rng(31)
+    n = k = 6
+    p, z = _rand_instance(rng, n)
+    c = D.c_weights(p, z, 0.4)
+    ok, a_lp = D.cyclic_row_sum_feasible(c, k, k)          # s = k: every worker may hold everything
+    assert ok
+    assert np.allclose(a_lp.sum(axis=1), D.row_targets(c, k), atol=1e-9)
+    assert np.allclose(a_lp.sum(axis=0), 1.0, atol=1e-9)
+    a_qp, supp = D.cyclic_code_optimal(c, k, k)
+    best = k * k / np.sum(1.0 / c)                          # Lemma 2 / Theorem 1 value
+    assert abs(D.csp2_objective(c, a_qp) - best) <= 1e-8 * best
+    assert abs(D.csp2_objective(c, a_lp) - best) <= 1e-9 * best
+
+
+def test_cyclic_optimum_equal_workers_is_uniform():
+    n = k = 8
+    c = np.full(n, 0.7)
+    for s in (1, 2, 3):
+        a, supp = D.cyclic_code_optimal(c, k, s)
+        assert np.allclose(a.sum(axis=1), 1.0, atol=1e-7)             # Y_i = 1 for equal workers
+        assert abs(D.csp2_objective(c, a) - n * 0.7) <= 1e-9 * n
+
+
+def test_cyclic_optimum_narrow_band_is_between_bound_and_heuristic_and_satisfies_kkt():
+    rng = np.random.default_rng(32)
+    hit_infeasible = False
+    for trial in range(6):
+        n = k = 10
+        s = 2 + trial % 2
+        p = rng.uniform(0.02, 0.7, n)
+        z = rng.integers(2, 9, n)
+        c = D.c_weights(p, z, 0.4)
+        a, supp = D.cyclic_code_optimal(c, k, s)
+        assert np.allclose(a.sum(axis=0), 1.0, atol=1e-9) and a.min() >= 0
+        for i in range(n):
+            assert all(a[i, j] == 0 for j in range(k) if j not in supp[i])
+        obj = D.csp2_objective(c, a)
+        bound = k * k / np.sum(1.0 / c)
+        heur = D.csp2_objective(c, D.cyclic_code(c, k, s)[0])
+        assert bound * (1 - 1e-9) <= obj <= heur * (1 + 1e-9)
+        assert _kkt_gap(c, a, supp, k) < 1e-5
+        ok, _ = D.cyclic_row_sum_feasible(c, k, s)
+        if ok:
+            assert abs(obj - bound) <= 1e-7 * bound
+        else:
+            hit_infeasible = True
+            assert obj > bound * (1 + 1e-6)
+    assert hit_infeasible                                     # the narrow band does bind somewhere
