@@ -145,6 +145,8 @@ def main():
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
     ap.add_argument("--bucket", type=int, default=0, choices=[0, 256],
                     help="256: one scale per 256-coordinate bucket (single pass over G); 0: one per vector")
+    ap.add_argument("--unfused", action="store_true",
+                    help="run the step as two passes (stand-alone decode kernel) instead of the fused pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=23,
                     help="the oracle is timed on the first 2^this coordinates (all partitions)")
@@ -172,7 +174,8 @@ def main():
 
     G = I.partial_gradients_torch(cfg, dev)
     assert G.stride(0) % 4 == 0 and G.data_ptr() % 16 == 0
-    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=args.bucket)
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=args.bucket,
+                      unfused_step=args.unfused)
     ctx.agc_set_code(*code)
     codes, scales, ghat = ctx.alloc_outputs(bits)
     nb = ctx.agc_scales_per_worker() if args.bucket else 0
@@ -210,8 +213,8 @@ def main():
     alg_bytes = {
         "scale_pass": 0.0 if args.bucket else 4.0 * k * d,
         "scale_finalize": 0.0,
-        "quantize": 4.0 * k * d + d * sum_b / 8.0 + 4.0 * n * nb,
-        "decode": d * arrived_b / 8.0 + 4.0 * d + 4.0 * n_arr * nb,
+        "quantize": 4.0 * k * d + d * sum_b / 8.0 + 4.0 * n * nb + (0.0 if args.unfused else 4.0 * d),
+        "decode": (d * arrived_b / 8.0 + 4.0 * d + 4.0 * n_arr * nb) if args.unfused else 0.0,
     }
     kernels = {}
     for name, (ms, cnt) in prof.items():
@@ -224,7 +227,8 @@ def main():
     dom_avg_s = kernels[dominant]["avg_ms"] * 1e-3
     achieved = alg_bytes[dominant] / dom_avg_s / 1e9
     step_alg_bytes = sum(alg_bytes.values())
-    tag = f"{cfg.name}_{args.code}_{args.scale}" + (f"_bucket{args.bucket}" if args.bucket else "")
+    tag = (f"{cfg.name}_{args.code}_{args.scale}" + (f"_bucket{args.bucket}" if args.bucket else "")
+           + ("_unfused" if args.unfused else ""))
     traffic, traffic_src = stored_traffic(tag, dominant)
     roofline = {
         "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -261,7 +265,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} workers, k={k} partitions, s={cfg.s}, d={d}, "
                                f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
                                f"{args.code} code, {args.scale} scale"
-                               + (f" per {args.bucket}-coordinate bucket" if args.bucket else " per vector"),
+                               + (f" per {args.bucket}-coordinate bucket" if args.bucket else " per vector")
+                               + (", two-pass step" if args.unfused else ", fused step"),
                    "code_path": ctx.agc_code_path()},
         "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
         "roofline": roofline,

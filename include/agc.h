@@ -70,7 +70,9 @@ typedef struct {
     int bucket;        /* 0: one scale per coded vector (the paper's quantizer).  256: one scale per
                           256-coordinate bucket (Sec. II-B names the bucket-wise extension): the
                           scales array becomes n x ceil(d/256) and the worker side reads G once */
-    int reserved[4];   /* must be zero */
+    int unfused_step;  /* non-zero: agc_step runs agc_encode_quantize then agc_decode as two passes;
+                          zero: one fused pass (same results bit for bit, see agc_step) */
+    int reserved[3];   /* must be zero */
 } agc_opts;
 
 /* --------------------------------------------------------------------------------------
@@ -171,7 +173,10 @@ agc_status agc_decode2(agc_ctx *ctx, void *const *codes_dev, const float *scales
                        const uint8_t *bits_host, const float *w_host, const float *v_host,
                        const uint8_t *mask_host, float *ghat_dev, float *ghat2_dev, void *hip_stream);
 
-/* One whole pass: agc_encode_quantize followed by agc_decode on the same stream. */
+/* One whole pass, with the outputs of agc_encode_quantize followed by agc_decode on the same
+ * stream (codes, scales, g_hat; identical bits).  By default the quantize kernel also forms
+ * g_hat from the codes it has just produced, in the order and arithmetic of agc_decode, so the
+ * payload is written but not read back; agc_opts.unfused_step selects the two-pass form. */
 agc_status agc_step(agc_ctx *ctx, const float *G_dev, int64_t ldg, const uint8_t *bits_host,
                     const float *w_host, const uint8_t *mask_host, uint64_t seed, uint64_t step,
                     void *const *codes_dev, float *scales_dev, float *ghat_dev, void *hip_stream);

@@ -30,7 +30,7 @@ EXPORTS = [
 
 class AgcOpts(C.Structure):
     _fields_ = [("scale_mode", C.c_int), ("allow_1bit", C.c_int), ("force_generic", C.c_int),
-                ("bucket", C.c_int), ("reserved", C.c_int * 4)]
+                ("bucket", C.c_int), ("unfused_step", C.c_int), ("reserved", C.c_int * 3)]
 
 
 class AgcError(RuntimeError):
@@ -254,11 +254,12 @@ def _stream_handle(stream):
 class Context:
     """Owns an agc_ctx and, for convenience, torch buffers for codes / scales / g_hat."""
 
-    def __init__(self, n, k, d, scale_mode=AGC_SCALE_MAXABS, allow_1bit=False, force_generic=False, bucket=0):
+    def __init__(self, n, k, d, scale_mode=AGC_SCALE_MAXABS, allow_1bit=False, force_generic=False, bucket=0,
+                 unfused_step=False):
         self.lib = load()
         self.n, self.k, self.d, self.bucket = int(n), int(k), int(d), int(bucket)
         opts = AgcOpts(int(scale_mode), int(bool(allow_1bit)), int(bool(force_generic)), int(bucket),
-                       (C.c_int * 4)())
+                       int(bool(unfused_step)), (C.c_int * 3)())
         h = _vp()
         st = self.lib.agc_create(C.byref(h), self.n, self.k, self.d, C.byref(opts))
         if st != AGC_OK:

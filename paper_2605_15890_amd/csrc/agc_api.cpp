@@ -208,6 +208,7 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
         if (e == hipSuccess) e = dev_alloc(&c->ws.super_sq, (size_t)c->ws.nsuper * n);
     }
     if (e == hipSuccess) e = dev_alloc(&c->ws.wq, (size_t)n);
+    if (e == hipSuccess) e = dev_alloc(&c->ws.wf, (size_t)n);
     if (e == hipSuccess) e = dev_alloc(&c->ws.wd, (size_t)n);
     if (e == hipSuccess) e = dev_alloc(&c->ws.coef2, (size_t)n);
     if (e != hipSuccess) {
@@ -228,6 +229,7 @@ void agc_destroy(agc_ctx* c)
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
     if (c->ws.wq) (void)hipFree(c->ws.wq);
+    if (c->ws.wf) (void)hipFree(c->ws.wf);
     if (c->ws.wd) (void)hipFree(c->ws.wd);
     if (c->ws.coef2) (void)hipFree(c->ws.coef2);
     if (c->ws.srow) (void)hipFree(c->ws.srow);
@@ -285,9 +287,14 @@ int agc_code_path(const agc_ctx* c)
     return c->opts.force_generic ? 0 : c->band;
 }
 
-agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits,
-                               uint64_t seed, uint64_t step, void* const* codes, float* scales,
-                               void* hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Worker side of a step.  sw.fuse != 0 (agc_step): the quantize pass also forms ghat.
+agc_status encode_quantize_impl(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits,
+                                uint64_t seed, uint64_t step, void* const* codes, float* scales,
+                                const agc::StepWeights& sw, float* ghat, void* hip_stream)
 {
     if (!c) return AGC_EINVAL;
     if (!c->has_code) return fail(c, AGC_ESTATE, "agc_set_code() has not been called");
@@ -310,8 +317,8 @@ agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const ui
     if (c->opts.bucket) {  // one pass: every block finds its own scale
         KernelTimer t{c, 2, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_quantize_bucket(G, ldg, c->n, c->k, c->d, code, c->opts.scale_mode, qs, c->ws, scales,
-                                        seed, step, stream);
+        e = agc::launch_quantize_bucket(G, ldg, c->n, c->k, c->d, code, c->opts.scale_mode, qs, sw, c->ws, scales,
+                                        seed, step, ghat, stream);
         if (e != hipSuccess) return hip_fail(c, e, "bucket-wise quantize launch");
         return t.end();
     }
@@ -325,18 +332,30 @@ agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const ui
     {
         KernelTimer t{c, 1, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, qs, c->ws, scales, stream);
+        e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, qs, sw, c->ws, scales, stream);
         if (e != hipSuccess) return hip_fail(c, e, "scale finalize launch");
         if ((st = t.end()) != AGC_OK) return st;
     }
     {
         KernelTimer t{c, 2, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, stream);
+        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, ghat, stream);
         if (e != hipSuccess) return hip_fail(c, e, "quantize launch");
         if ((st = t.end()) != AGC_OK) return st;
     }
     return AGC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+agc_status agc_encode_quantize(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits,
+                               uint64_t seed, uint64_t step, void* const* codes, float* scales,
+                               void* hip_stream)
+{
+    agc::StepWeights sw{};
+    return encode_quantize_impl(c, G, ldg, bits, seed, step, codes, scales, sw, nullptr, hip_stream);
 }
 
 agc_status agc_decode(agc_ctx* c, void* const* codes, const float* scales, const uint8_t* bits,
@@ -418,9 +437,20 @@ agc_status agc_step(agc_ctx* c, const float* G, int64_t ldg, const uint8_t* bits
     // validate the decode arguments before anything is enqueued
     if (!w || !mask || !ghat) return fail(c, AGC_EINVAL, "null argument");
     if (reinterpret_cast<uintptr_t>(ghat) & 15u) return fail(c, AGC_EALIGN, "ghat_dev is not 16-byte aligned");
-    agc_status st = agc_encode_quantize(c, G, ldg, bits, seed, step, codes, scales, hip_stream);
-    if (st != AGC_OK) return st;
-    return agc_decode(c, codes, scales, bits, w, mask, ghat, hip_stream);
+    if (c->opts.unfused_step) {
+        agc_status st = agc_encode_quantize(c, G, ldg, bits, seed, step, codes, scales, hip_stream);
+        if (st != AGC_OK) return st;
+        return agc_decode(c, codes, scales, bits, w, mask, ghat, hip_stream);
+    }
+    // fused: the quantize pass forms the estimate from the codes it has just produced (the codes
+    // are still written: they are the payload), which saves the decode kernel's read of them
+    agc::StepWeights sw{};
+    sw.fuse = 1;
+    for (int i = 0; i < c->n; ++i) {
+        sw.w[i] = w[i];
+        sw.arrived[i] = mask[i] ? 1 : 0;
+    }
+    return encode_quantize_impl(c, G, ldg, bits, seed, step, codes, scales, sw, ghat, hip_stream);
 }
 
 int64_t agc_ls_workspace_floats(int64_t n_rows, int n_feat, int k_parts)

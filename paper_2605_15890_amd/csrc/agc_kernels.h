@@ -24,6 +24,13 @@ struct WorkerQ {
     void* codes;          // packed stream of the worker
 };
 
+// what the fused quantize+decode pass additionally needs: the decode weight of worker i
+// (w_i * scale_i / L_i; with bucket-wise scales w_i / L_i) and whether it arrived
+struct WorkerF {
+    float coef;
+    uint32_t arrived;
+};
+
 // one arrived worker as the decode pass sees it
 struct WorkerD {
     const void* codes;
@@ -37,6 +44,7 @@ struct Workspace {
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
     WorkerQ* wq;          // [n]  written by the scale finalize
+    WorkerF* wf;          // [n]  written with wq when the step runs fused
     WorkerD* wd;          // [n]  arrived workers, compacted, written by the decode prologue
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker
@@ -46,6 +54,12 @@ struct Workspace {
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];
     uint8_t bits[kArgWorkers];
+};
+
+struct StepWeights {       // decode side of a fused step, as kernel arguments of the table kernels
+    float w[kArgWorkers];
+    uint8_t arrived[kArgWorkers];
+    int fuse;              // 0: plain encode+quantize, the two arrays are ignored
 };
 
 struct DecodeStreams {     // host arrays of the decode call, as kernel arguments of its prologue
@@ -66,17 +80,21 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream);
 // K1f: partials -> scales[n] and the per-worker table of the quantize pass.
-hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
+// sw.fuse != 0: the quantize pass that follows also forms the estimate (ghat) from the codes it
+// has just produced, in the same order and arithmetic as the decode kernel.
+hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream);
 // K2: fused encode + stochastic quantize + bit-pack.
+// ghat != nullptr: fused step (the table must have been written with sw.fuse != 0).
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           hipStream_t stream);
+                           float* ghat, hipStream_t stream);
 // Bucket-wise scales (one per 256-coordinate block and worker): a table prologue, then ONE pass
 // over G that derives each block's scale from the block itself.  scales: n x nb, nb = ceil(d/256).
 hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,
-                                  int scale_mode, const QuantStreams& out, const Workspace& ws, float* scales,
-                                  uint64_t seed, uint64_t step, hipStream_t stream);
+                                  int scale_mode, const QuantStreams& out, const StepWeights& sw,
+                                  const Workspace& ws, float* scales, uint64_t seed, uint64_t step, float* ghat,
+                                  hipStream_t stream);
 // K3: table of the arrived workers (a one-workgroup prologue), then masked dequantize +
 // weighted sum.
 // nb = 0: one scale per worker; nb > 0: scales is n x nb, one scale per 256-coordinate bucket.

@@ -158,7 +158,7 @@ __device__ __forceinline__ float inv16_of(float scale, int bits)
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStreams out,
+__global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStreams out, StepWeights sw,
                                                                Workspace ws, float* scales)
 {
     const int i = blockIdx.x;
@@ -223,14 +223,18 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
         scales[i] = scale;
         const int b = out.bits[i];
         ws.wq[i] = WorkerQ{inv16_of(scale, b), (uint32_t)b, out.codes[i]};
+        if (sw.fuse) {  // decode weight of one grid unit, as the decode prologue forms it
+            const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+            ws.wf[i] = WorkerF{(float)(((double)sw.w[i] * (double)scale) / L), (uint32_t)sw.arrived[i]};
+        }
     }
 }
 
-hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
+hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
-    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, ws, scales);
-    else hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, ws, scales);
+    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
+    else hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
     return hipGetLastError();
 }
 
@@ -244,6 +248,7 @@ struct QuantArgs {
     uint32_t key0, key1, step_lo, step_hi;
     float* scales;  // bucket-wise scales only: n x nb
     int64_t nb;
+    float* ghat;    // fused step only
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
@@ -291,7 +296,10 @@ __device__ __forceinline__ void wave_lds_fence()
 // BUCKET 1 / 2: one scale per 256-coordinate block, derived here from the block itself (largest
 // magnitude / Euclidean norm), stored by lane 0, and turned into the multiplier with one binary32
 // division (Sec. II-B names the bucket-wise extension; this is its single-pass form).
-template <int BUCKET>
+// FUSE: the pass also accumulates the master's estimate (Sec. II-A aggregation) from the codes it
+// has just formed: arrived workers in ascending order, one fused multiply-add each from 0, the
+// arithmetic of the stand-alone decode kernel, so both give the same bits.
+template <int BUCKET, bool FUSE>
 struct EpiQuant {
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
@@ -305,10 +313,11 @@ struct EpiQuant {
     uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
     float* scales;          // bucket-wise scales: n x nb
     int64_t nb;
+    const WorkerF* __restrict__ wf;
+    float acc[4];           // fused step: this lane's four coordinates of the estimate
 
-    __device__ __forceinline__ float block_multiplier(int i, const float4& f, int b)
+    __device__ __forceinline__ float block_multiplier(int i, const float4& f, int b, float& scale)
     {
-        float scale;
         if (BUCKET == 1) {
             const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
             scale = __uint_as_float(wave_max_nonneg_bits(a));
@@ -327,7 +336,7 @@ struct EpiQuant {
     // four rounding decisions; only the grid position differs between the regular grid
     // (b >= 2) and the two-point grid of a one-bit worker
     __device__ __forceinline__ void codes4(int i, const float4& f, float inv, int b, uint32_t wa,
-                                           uint32_t wb, uint32_t (&c)[4])
+                                           uint32_t wb, uint32_t (&c)[4], uint32_t (&lev)[4])
     {
         const float fv[4] = {f.x, f.y, f.z, f.w};
         const uint32_t u[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
@@ -351,6 +360,8 @@ struct EpiQuant {
             for (int q = 0; q < 4; ++q)
                 if (tie[q]) c[q] = round_tied(T[q], r2[q], L);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lev[q] = c[q];
 #pragma unroll
         for (int q = 0; q < 4; ++q) c[q] |= (__float_as_uint(fv[q]) >> ((32 - b) & 31)) & signbit;
         if (wave_ragged) {  // codes of coordinates >= d are zero padding
@@ -377,9 +388,24 @@ struct EpiQuant {
         }
         const WorkerQ q = wq[i];  // wave-uniform: one scalar 16-byte load
         const int b = (int)q.bits;
-        uint32_t c[4];
-        const float inv = BUCKET == 0 ? q.inv16 : block_multiplier(i, f, b);
-        codes4(i, f, inv, b, wa, wb, c);
+        uint32_t c[4], lev[4];
+        float scale = 0.f;
+        const float inv = BUCKET == 0 ? q.inv16 : block_multiplier(i, f, b, scale);
+        codes4(i, f, inv, b, wa, wb, c, lev);
+        if constexpr (FUSE) {
+            const WorkerF wk = wf[i];  // wave-uniform scalar load
+            if (wk.arrived) {
+                const float coef = BUCKET == 0 ? wk.coef : wk.coef * scale;
+                const float fv[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float v;
+                    if (b >= 2) v = __uint_as_float(__float_as_uint((float)lev[t]) | (__float_as_uint(fv[t]) & 0x80000000u));
+                    else v = lev[t] ? 1.0f : -1.0f;
+                    acc[t] = fmaf(coef, v, acc[t]);
+                }
+            }
+        }
 
         // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
         const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
@@ -419,12 +445,13 @@ struct EpiQuant {
     }
 };
 
-template <int S, int BUCKET>
+template <int S, int BUCKET, bool FUSE>
 __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,
-                                                         const WorkerQ* __restrict__ wq, QuantArgs a)
+                                                         const WorkerQ* __restrict__ wq,
+                                                         const WorkerF* __restrict__ wf, QuantArgs a)
 {
     __shared__ uint32_t lds_stage[kWavesPerWg][kStageWords];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
@@ -436,68 +463,90 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
     if (base >= a.d) return;
     const LaneCoords lc = lane_coords(base, lane, a.d);
     const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
-    EpiQuant<BUCKET> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
-                         groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
-                         lc.wave_ragged, 0u, 0u, a.scales, a.nb};
+    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
+                               groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
+                               lc.wave_ragged, 0u, 0u, a.scales, a.nb, wf, {0.f, 0.f, 0.f, 0.f}};
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
+    if constexpr (FUSE) {
+        float* dst = a.ghat + base + 4 * lane;
+        if (lc.nvalid == 4) {
+            *reinterpret_cast<float4*>(dst) = make_float4(epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (t < lc.nvalid) dst[t] = epi.acc[t];
+        }
+    }
 }
 
 template <int S, int BUCKET>
-static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const WorkerQ* wq,
+static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const Workspace& ws,
                                     const QuantArgs& a, hipStream_t stream)
 {
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
-    hipLaunchKernelGGL((k_quantize<S, BUCKET>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
-                       code.col, code.val, wq, a);
+    if (a.ghat)
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, ws.wq, ws.wf, a);
+    else
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, ws.wq, ws.wf, a);
     return hipGetLastError();
 }
 
 template <int BUCKET>
-static hipError_t launch_quantize_band(const float* G, const CodeDev& code, const WorkerQ* wq,
+static hipError_t launch_quantize_band(const float* G, const CodeDev& code, const Workspace& ws,
                                        const QuantArgs& a, hipStream_t stream)
 {
     switch (code.band) {
-        case 1: return launch_quantize_s<1, BUCKET>(G, code, wq, a, stream);
-        case 2: return launch_quantize_s<2, BUCKET>(G, code, wq, a, stream);
-        case 3: return launch_quantize_s<3, BUCKET>(G, code, wq, a, stream);
-        case 4: return launch_quantize_s<4, BUCKET>(G, code, wq, a, stream);
-        case 5: return launch_quantize_s<5, BUCKET>(G, code, wq, a, stream);
-        case 6: return launch_quantize_s<6, BUCKET>(G, code, wq, a, stream);
-        case 7: return launch_quantize_s<7, BUCKET>(G, code, wq, a, stream);
-        case 8: return launch_quantize_s<8, BUCKET>(G, code, wq, a, stream);
-        default: return launch_quantize_s<0, BUCKET>(G, code, wq, a, stream);
+        case 1: return launch_quantize_s<1, BUCKET>(G, code, ws, a, stream);
+        case 2: return launch_quantize_s<2, BUCKET>(G, code, ws, a, stream);
+        case 3: return launch_quantize_s<3, BUCKET>(G, code, ws, a, stream);
+        case 4: return launch_quantize_s<4, BUCKET>(G, code, ws, a, stream);
+        case 5: return launch_quantize_s<5, BUCKET>(G, code, ws, a, stream);
+        case 6: return launch_quantize_s<6, BUCKET>(G, code, ws, a, stream);
+        case 7: return launch_quantize_s<7, BUCKET>(G, code, ws, a, stream);
+        case 8: return launch_quantize_s<8, BUCKET>(G, code, ws, a, stream);
+        default: return launch_quantize_s<0, BUCKET>(G, code, ws, a, stream);
     }
 }
 
 // table of the bucket-wise pass: bit-width and stream of every worker (the multiplier is
 // found per block inside the pass)
-__global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams out, WorkerQ* wq)
+__global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams out, StepWeights sw, WorkerQ* wq,
+                                                            WorkerF* wf)
 {
     const int i = threadIdx.x;
-    if (i < n) wq[i] = WorkerQ{0.0f, (uint32_t)out.bits[i], out.codes[i]};
+    if (i >= n) return;
+    const int b = out.bits[i];
+    wq[i] = WorkerQ{0.0f, (uint32_t)b, out.codes[i]};
+    if (sw.fuse) {
+        const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+        wf[i] = WorkerF{(float)((double)sw.w[i] / L), (uint32_t)sw.arrived[i]};
+    }
 }
 
 hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,
-                                  int scale_mode, const QuantStreams& out, const Workspace& ws, float* scales,
-                                  uint64_t seed, uint64_t step, hipStream_t stream)
+                                  int scale_mode, const QuantStreams& out, const StepWeights& sw,
+                                  const Workspace& ws, float* scales, uint64_t seed, uint64_t step, float* ghat,
+                                  hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_quant_table, dim3(1), dim3(kWgThreads), 0, stream, n, out, ws.wq);
+    hipLaunchKernelGGL(k_quant_table, dim3(1), dim3(kWgThreads), 0, stream, n, out, sw, ws.wq, ws.wf);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                scales, (d + kBlockCoords - 1) / kBlockCoords};
-    return scale_mode == 0 ? launch_quantize_band<2>(G, code, ws.wq, a, stream)
-                           : launch_quantize_band<1>(G, code, ws.wq, a, stream);
+                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat};
+    return scale_mode == 0 ? launch_quantize_band<2>(G, code, ws, a, stream)
+                           : launch_quantize_band<1>(G, code, ws, a, stream);
 }
 
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           hipStream_t stream)
+                           float* ghat, hipStream_t stream)
 {
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                nullptr, 0};
-    return launch_quantize_band<0>(G, code, ws.wq, a, stream);
+                nullptr, 0, ghat};
+    return launch_quantize_band<0>(G, code, ws, a, stream);
 }
 
 // =======================================================================================

@@ -206,12 +206,13 @@ def test_argument_errors_are_reported_not_launched():
     ctx.close()
 
 
-def test_per_kernel_timing_counts_launches():
+@pytest.mark.parametrize("unfused", [True, False])
+def test_per_kernel_timing_counts_launches(unfused):
     import torch
     rng = np.random.default_rng(3)
     n = k = 4
     d = 1 << 16
-    ctx = api.Context(n, k, d)
+    ctx = api.Context(n, k, d, unfused_step=unfused)
     ctx.agc_set_code(*cyclic_csr(rng, n, 2))
     bits = np.array([2, 3, 4, 5], dtype=np.uint8)
     codes, scales, ghat = ctx.alloc_outputs(bits)
@@ -222,7 +223,10 @@ def test_per_kernel_timing_counts_launches():
     prof = ctx.agc_profile_read()
     for name in api.KERNEL_NAMES:
         ms, cnt = prof[name]
-        assert cnt == 150 and 0 < ms < 10_000
+        if name == "decode" and not unfused:      # the fused step has no separate decode launch
+            assert cnt == 0
+        else:
+            assert cnt == 150 and 0 < ms < 10_000
     ctx.agc_profile_enable(False)
     ctx.agc_step(G, bits, np.ones(n, np.float32), np.ones(n, np.uint8), 1, 0, codes, scales, ghat)
     torch.cuda.synchronize()
@@ -277,3 +281,35 @@ def test_optimal_cyclic_code_runs_on_the_band_path():
                       expect_path=cfg.s)
         compare_with_oracle(G, cfg.k, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 1, scale_mode, out,
                             tag=f"optimal cyclic mode={scale_mode}")
+
+
+@pytest.mark.parametrize("bucket", [0, 256])
+def test_fused_step_equals_two_pass_step(bucket):
+    """agc_step forms the estimate inside the quantize pass; with unfused_step it runs the
+    stand-alone decode kernel.  Codes, scales and estimate must agree bit for bit (ragged size,
+    mixed widths including one bit, a straggler, band and generic path, both scale kinds)."""
+    import torch
+    rng = np.random.default_rng(21)
+    n = k = 7
+    d = 3 * 1024 + 333
+    bits = np.array([1, 2, 3, 4, 7, 9, 16], dtype=np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    G = to_device(rng.standard_normal((k, d)).astype(np.float32))
+    for code in (cyclic_csr(rng, n, 3), random_csr(rng, n, k, 4)):
+        for scale_mode in MODES:
+            for mask in (np.array([1, 1, 0, 1, 0, 1, 1], np.uint8), np.zeros(n, np.uint8)):
+                outs = []
+                for unfused in (False, True):
+                    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=True, bucket=bucket,
+                                      unfused_step=unfused)
+                    ctx.agc_set_code(*code)
+                    codes, scales, ghat = ctx.alloc_outputs(bits)
+                    ghat.fill_(float("nan"))
+                    ctx.agc_step(G, bits, w, mask, 9, 4, codes, scales, ghat)
+                    torch.cuda.synchronize()
+                    outs.append((codes, scales, ghat))
+                    ctx.close()
+                (c0, s0, g0), (c1, s1, g1) = outs
+                assert all(torch.equal(a, b) for a, b in zip(c0, c1))
+                assert torch.equal(s0.view(torch.int32), s1.view(torch.int32))
+                assert torch.equal(g0.view(torch.int32), g1.view(torch.int32))

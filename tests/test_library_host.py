@@ -43,9 +43,9 @@ def test_create_rejects_bad_shapes_without_touching_the_gpu():
         assert lib.agc_create(ctypes.byref(h), n, k, d, None) == api.AGC_ESHAPE
         assert not h.value
     assert lib.agc_create(None, 4, 4, 16, None) == api.AGC_EINVAL
-    bad = api.AgcOpts(7, 0, 0, 0, (ctypes.c_int * 4)())
+    bad = api.AgcOpts(7, 0, 0, 0, 0, (ctypes.c_int * 3)())
     assert lib.agc_create(ctypes.byref(h), 4, 4, 16, ctypes.byref(bad)) == api.AGC_EINVAL
-    bad = api.AgcOpts(api.AGC_SCALE_MAXABS, 0, 0, 512, (ctypes.c_int * 4)())     # only 256-coordinate buckets
+    bad = api.AgcOpts(api.AGC_SCALE_MAXABS, 0, 0, 512, 0, (ctypes.c_int * 3)())     # only 256-coordinate buckets
     assert lib.agc_create(ctypes.byref(h), 4, 4, 16, ctypes.byref(bad)) == api.AGC_EINVAL
 
 
