@@ -145,10 +145,20 @@ __device__ __forceinline__ LaneCoords lane_coords(int64_t base, int lane, int64_
 // the load is a scalar base plus a 32-bit lane offset.  Every lane loads (lanes past d re-read
 // the last float4), so there is no per-lane predicate; with RAGGED the coordinates >= d are
 // zeroed, without it the caller guarantees that the whole block lies inside the vector.
-template <bool RAGGED>
+// STREAM: the element is used once per pass (register-ring driver); a non-temporal load keeps it
+// from displacing anything in the caches (measured: 9 % off the scale pass).  The gather driver
+// re-reads rows and wants them cached.
+template <bool RAGGED, bool STREAM = false>
 __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const LaneCoords& lc)
 {
-    float4 v = reinterpret_cast<const float4*>(row)[lc.lane4];
+    float4 v;
+    if (STREAM) {
+        typedef float f32x4_t __attribute__((ext_vector_type(4)));
+        const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(row) + lc.lane4);
+        v = make_float4(t.x, t.y, t.z, t.w);
+    } else {
+        v = reinterpret_cast<const float4*>(row)[lc.lane4];
+    }
     if (RAGGED) {
         if (lc.nvalid < 1) v.x = 0.f;
         if (lc.nvalid < 2) v.y = 0.f;
@@ -230,11 +240,11 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
     constexpr int R = RingShape<S>::R;
     const int j = j0 + r;
     if (STEADY) {
-        ring[(r + P) % R] = load_row4<false>(next_row, lc);
+        ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
         next_row += (j + P + 1 < k) ? ldg : 0;  // stays on the last row once it is reached
     } else {
         if (j + P < k) {  // prefetch the row that arrives P steps from now
-            ring[(r + P) % R] = load_row4<false>(next_row, lc);
+            ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
             next_row += (j + P + 1 < k) ? ldg : 0;
         }
         if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
@@ -281,7 +291,7 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
 #pragma unroll
     for (int r = 0; r < P; ++r) {
         if (r < k) {
-            ring[r] = load_row4<false>(next_row, lc);
+            ring[r] = load_row4<false, true>(next_row, lc);
             next_row += (r + 1 < k) ? ldg : 0;
         }
     }

@@ -434,12 +434,12 @@ struct EpiQuant {
         {
             const uint32_t v = stage[lane];
             if (lane < nwords) stage[lane] = 0u;
-            if (lane < nstore) dst[lane] = v;
+            if (lane < nstore) __builtin_nontemporal_store(v, dst + lane);  // the payload is not read again
         }
         if (b > 8) {
             const uint32_t v = stage[lane + kWave];
             if (lane + kWave < nwords) stage[lane + kWave] = 0u;
-            if (lane + kWave < nstore) dst[lane + kWave] = v;
+            if (lane + kWave < nstore) __builtin_nontemporal_store(v, dst + lane + kWave);
         }
         wave_lds_fence();
     }
@@ -599,7 +599,7 @@ __device__ __forceinline__ void decode_words(const global_u32* __restrict__ src,
 {
     uint32_t w[B];
 #pragma unroll
-    for (int t = 0; t < B; ++t) w[t] = src[t];
+    for (int t = 0; t < B; ++t) w[t] = __builtin_nontemporal_load(src + t);  // each code word is read once
 #pragma unroll
     for (int q = 0; q < kDecCoords; ++q) {
         const int bit = q * B;
