@@ -52,7 +52,7 @@ typedef enum {
     AGC_EINVAL = -1, /* null pointer, non-positive size, unknown option value */
     AGC_ESHAPE = -2, /* n, k, d out of range; CSR malformed; column index out of range */
     AGC_EBITS = -3,  /* bit-width outside [2,16] (or 1 without allow_1bit) */
-    AGC_EALIGN = -4, /* G or g_hat not 16-byte aligned, ldg not a multiple of 4, stream not 4-byte aligned */
+    AGC_EALIGN = -4, /* G or g_hat not 16-byte aligned, ldg not a multiple of 4, stream not 16-byte aligned */
     AGC_ENOMEM = -5, /* workspace allocation failed */
     AGC_EHIP = -6,   /* a HIP call failed (message in agc_last_error) */
     AGC_ESTATE = -7  /* agc_set_code() has not been called */
@@ -138,7 +138,7 @@ const char *agc_last_error(const agc_ctx *ctx);
  *              ldg % 4 == 0, base 16-byte aligned); read-only
  *   bits_host  host, n bytes
  *   codes_dev  host array of n device pointers; stream i has agc_code_bytes(d, b_i) bytes,
- *              4-byte aligned; fully overwritten, padding included
+ *              16-byte aligned; fully overwritten, padding included
  *   scales_dev device, n floats; overwritten
  */
 agc_status agc_encode_quantize(agc_ctx *ctx, const float *G_dev, int64_t ldg,

@@ -10,11 +10,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagc.so")
-SOURCES = ["agc_kernels.hip", "agc_ls_kernels.hip", "agc_api.cpp", "agc_host.cpp"]
+SOURCES = ["agc_kernels.hip", "agc_quantize_b0.hip", "agc_quantize_b1.hip", "agc_quantize_b2.hip",
+           "agc_ls_kernels.hip", "agc_api.cpp", "agc_host.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+OBJ_DIR = os.path.join(HERE, "_build")
+
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",            # every binary32 statement is one rounding; fma only where written
     "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
@@ -40,15 +43,39 @@ def hip_runtime_link_flags():
     return flags
 
 
-def build(verbose: bool = True, extra=()) -> str:
-    cmd = [HIPCC, *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB,
-           *hip_runtime_link_flags()]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+def _newest_input():
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "agc.h")]
+    return max(os.path.getmtime(f) for f in deps)
+
+
+def build(verbose: bool = True, extra=(), incremental: bool = False) -> str:
+    """Compiles every source to an object (in parallel) and links libagc.so.  incremental=True
+    skips objects that are newer than every file under csrc/ and the public header (a
+    convenience while editing; the default compiles everything)."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    newest = _newest_input()
+    jobs = []
+    for src in SOURCES:
+        obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+        if incremental and not extra and os.path.exists(obj) and os.path.getmtime(obj) > newest:
+            continue
+        jobs.append([HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        list(pool.map(run, jobs))
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+    run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, *hip_runtime_link_flags()])
     return LIB
 
 
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    args = sys.argv[1:]
+    inc = "--incremental" in args
+    build(extra=[a for a in args if a != "--incremental"], incremental=inc)
     print(LIB)

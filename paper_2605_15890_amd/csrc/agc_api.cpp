@@ -139,8 +139,8 @@ agc_status check_streams(agc_ctx* c, void* const* codes)
 {
     for (int i = 0; i < c->n; ++i) {
         if (!codes[i]) return fail(c, AGC_EINVAL, "codes_dev[" + std::to_string(i) + "] is null");
-        if (reinterpret_cast<uintptr_t>(codes[i]) & 3u)
-            return fail(c, AGC_EALIGN, "codes_dev[" + std::to_string(i) + "] is not 4-byte aligned");
+        if (reinterpret_cast<uintptr_t>(codes[i]) & 15u)
+            return fail(c, AGC_EALIGN, "codes_dev[" + std::to_string(i) + "] is not 16-byte aligned");
     }
     return AGC_OK;
 }

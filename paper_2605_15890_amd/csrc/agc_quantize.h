@@ -1,0 +1,292 @@
+// K2 of the worker side: streaming encode + stochastic quantize + bit-pack (+ the fused estimate).
+// Template code only; agc_quantize_b0/b1/b2.hip instantiate it for the three ways a block gets
+// its multiplier, so that the three sets of kernels compile in parallel.
+#pragma once
+
+#include "agc_device.h"
+#include "agc_kernels.h"
+
+namespace agc {
+
+// =======================================================================================
+// K2  encode + stochastic quantize + bit-pack
+// =======================================================================================
+struct QuantArgs {
+    int64_t ldg;
+    int n, k;
+    int64_t d;
+    uint32_t key0, key1, step_lo, step_hi;
+    float* scales;  // bucket-wise scales only: n x nb
+    int64_t nb;
+    float* ghat;    // fused step only
+};
+
+typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
+
+constexpr int kStageWords = 8 * 16 + 4;  // 256 codes of up to 16 bits, plus spill of zero bits; 16-byte multiple
+
+// One rounding decision (Sec. II-B): T is the grid position scaled by 2^16; the cell is
+// T >> 16, the low 16 bits are the first 16 bits of the round-up probability, compared with
+// the 16-bit primary draw; equality is a tie, resolved later by a secondary draw.
+__device__ __forceinline__ uint32_t round_primary(float T, uint32_t u16, uint32_t L, bool& tie)
+{
+    const uint32_t Ti = (uint32_t)T;
+    const uint32_t lo = Ti >> 16, Fi = Ti & 0xFFFFu;
+    tie = (u16 == Fi);
+    const uint32_t level = lo + (u16 < Fi ? 1u : 0u);
+    return level < L ? level : L;
+}
+
+// the same decision for a coordinate whose primary draw tied: U < (Fi+g)/2^16 <=> r2 < g*2^32
+__device__ __forceinline__ uint32_t round_tied(float T, uint32_t r2, uint32_t L)
+{
+    const uint32_t Ti = (uint32_t)T;
+    const float g = T - (float)Ti;
+    const uint32_t up = ((double)r2 < (double)g * 4294967296.0) ? 1u : 0u;
+    const uint32_t level = (Ti >> 16) + up;
+    return level < L ? level : L;
+}
+
+template <bool ONEBIT>
+__device__ __forceinline__ float grid_pos(float f, float inv)
+{
+    if (ONEBIT) return fmaxf(fmaf(f, inv, 32768.0f), 0.0f);
+    return fabsf(f) * inv;
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wave execute in issue order; this only pins the compiler's order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// BUCKET 0: the worker's multiplier comes from the table (one scale per vector).
+// BUCKET 1 / 2: one scale per 256-coordinate block, derived here from the block itself (largest
+// magnitude / Euclidean norm), stored by lane 0, and turned into the multiplier with one binary32
+// division (Sec. II-B names the bucket-wise extension; this is its single-pass form).
+// FUSE: the pass also accumulates the master's estimate (Sec. II-A aggregation) from the codes it
+// has just formed: arrived workers in ascending order, one fused multiply-add each from 0, the
+// arithmetic of the stand-alone decode kernel, so both give the same bits.
+template <int BUCKET, bool FUSE>
+struct EpiQuant {
+    const WorkerQ* __restrict__ wq;
+    uint32_t key0, key1, step_lo, step_hi;
+    uint32_t* stage;     // this wave's LDS staging words, all zero between workers
+    int lane;
+    int64_t block;       // index of this wave's 256-coordinate block
+    int groups_valid;    // 128-code groups of this block that exist in the streams (1 or 2)
+    uint32_t ctr0;       // m >> 2 of this lane's coordinates
+    int nvalid;
+    bool wave_ragged;    // wave-uniform: some lane has coordinates >= d
+    uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
+    float* scales;          // bucket-wise scales: n x nb
+    int64_t nb;
+    const WorkerF* __restrict__ wf;
+    float acc[4];           // fused step: this lane's four coordinates of the estimate
+
+    __device__ __forceinline__ float block_multiplier(int i, const float4& f, int b, float& scale)
+    {
+        if (BUCKET == 1) {
+            const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+            scale = __uint_as_float(wave_max_nonneg_bits(a));
+        } else {
+            const double x0 = f.x, x1 = f.y, x2 = f.z, x3 = f.w;
+            const double s01 = x0 * x0 + x1 * x1;
+            const double s23 = x2 * x2 + x3 * x3;
+            scale = (float)sqrt(wave_butterfly_add(s01 + s23));
+        }
+        if (lane == 0) *((__attribute__((address_space(1))) float*)scales + ((int64_t)i * nb + block)) = scale;
+        const float num = b >= 2 ? (float)(((1u << (b - 1)) - 1u) << 16) : 32768.0f;
+        const float q = num / scale;  // correctly rounded binary32 division
+        return (scale > 0.0f && q <= 3.402823466e+38f) ? q : 0.0f;
+    }
+
+    // four rounding decisions; only the grid position differs between the regular grid
+    // (b >= 2) and the two-point grid of a one-bit worker
+    __device__ __forceinline__ void codes4(int i, const float4& f, float inv, int b, uint32_t wa,
+                                           uint32_t wb, uint32_t (&c)[4], uint32_t (&lev)[4])
+    {
+        const float fv[4] = {f.x, f.y, f.z, f.w};
+        const uint32_t u[4] = {wa & 0xFFFFu, wa >> 16, wb & 0xFFFFu, wb >> 16};
+        const uint32_t L = (b >= 2) ? ((1u << (b - 1)) - 1u) : 1u;
+        const uint32_t signbit = (b >= 2) ? (1u << (b - 1)) : 0u;
+        bool tie[4];
+        float T[4];
+        if (b >= 2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) T[q] = grid_pos<false>(fv[q], inv);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) T[q] = grid_pos<true>(fv[q], inv);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] = round_primary(T[q], u[q], L, tie[q]);
+        if (__any(tie[0] | tie[1] | tie[2] | tie[3])) {  // about one wave pass in 250
+            uint32_t r2[4];
+            philox4x32_10(ctr0, 0x80000000u | (uint32_t)i, step_lo, step_hi, key0, key1, r2);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (tie[q]) c[q] = round_tied(T[q], r2[q], L);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lev[q] = c[q];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) c[q] |= (__float_as_uint(fv[q]) >> ((32 - b) & 31)) & signbit;
+        if (wave_ragged) {  // codes of coordinates >= d are zero padding
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q >= nvalid) c[q] = 0u;
+        }
+    }
+
+    template <bool EVEN>
+    __device__ __forceinline__ void worker(int i, const float4& f)
+    {
+        uint32_t wa, wb;
+        if (EVEN) {
+            uint32_t o[4];
+            philox4x32_10(ctr0, (uint32_t)i >> 1, step_lo, step_hi, key0, key1, o);
+            wa = o[0];
+            wb = o[1];
+            keep2 = o[2];
+            keep3 = o[3];
+        } else {
+            wa = keep2;
+            wb = keep3;
+        }
+        const WorkerQ q = wq[i];  // wave-uniform: one scalar 16-byte load
+        const int b = (int)q.bits;
+        uint32_t c[4], lev[4];
+        float scale = 0.f;
+        const float inv = BUCKET == 0 ? q.inv16 : block_multiplier(i, f, b, scale);
+        codes4(i, f, inv, b, wa, wb, c, lev);
+        if constexpr (FUSE) {
+            const WorkerF wk = wf[i];  // wave-uniform scalar load
+            if (wk.arrived) {
+                const float coef = BUCKET == 0 ? wk.coef : wk.coef * scale;
+                const float fv[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float v;
+                    if (b >= 2) v = __uint_as_float(__float_as_uint((float)lev[t]) | (__float_as_uint(fv[t]) & 0x80000000u));
+                    else v = lev[t] ? 1.0f : -1.0f;
+                    acc[t] = fmaf(coef, v, acc[t]);
+                }
+            }
+        }
+
+        // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
+        const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
+        uint32_t* slot = stage + (bitpos >> 5);
+        const uint32_t sh = bitpos & 31u;
+        if (b <= 8) {
+            const uint32_t chunk = c[0] | (c[1] << b) | (c[2] << (2 * b)) | (c[3] << (3 * b));
+            const uint64_t v = (uint64_t)chunk << sh;
+            atomicOr(slot, (uint32_t)v);
+            atomicOr(slot + 1, (uint32_t)(v >> 32));
+        } else {
+            const uint64_t chunk = (uint64_t)c[0] | ((uint64_t)c[1] << b) | ((uint64_t)c[2] << (2 * b)) |
+                                   ((uint64_t)c[3] << (3 * b));
+            const uint64_t v = chunk << sh;
+            const uint32_t top = sh ? (uint32_t)(chunk >> (64 - sh)) : 0u;
+            atomicOr(slot, (uint32_t)v);
+            atomicOr(slot + 1, (uint32_t)(v >> 32));
+            atomicOr(slot + 2, top);
+        }
+        wave_lds_fence();
+        // the block's 8b words leave as one contiguous, coalesced store; the staging words
+        // are handed back zeroed
+        // (16 bytes per lane: 2b lanes cover the 8b words; the payload is not read again, so the
+        // store is non-temporal)
+        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+        if (lane < 2 * b) {
+            u32x4_t* sp = reinterpret_cast<u32x4_t*>(stage) + lane;
+            const u32x4_t v = *sp;
+            *sp = u32x4_t{0u, 0u, 0u, 0u};
+            if (lane < b * groups_valid) {
+                __attribute__((address_space(1))) u32x4_t* dst =
+                    (__attribute__((address_space(1))) u32x4_t*)q.codes + (block * (2 * b) + lane);
+                __builtin_nontemporal_store(v, dst);
+            }
+        }
+        wave_lds_fence();
+    }
+};
+
+template <int S, int BUCKET, bool FUSE>
+__global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict__ G,
+                                                         const int* __restrict__ row_ptr,
+                                                         const int* __restrict__ col,
+                                                         const float* __restrict__ val,
+                                                         const WorkerQ* __restrict__ wq,
+                                                         const WorkerF* __restrict__ wf, QuantArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t lds_stage[kWavesPerWg][kStageWords];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
+    const int lane = threadIdx.x % kWave;
+    const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
+    const int64_t base = block * (int64_t)kBlockCoords;
+    for (int w = lane; w < kStageWords; w += kWave) lds_stage[wave][w] = 0u;
+    wave_lds_fence();
+    if (base >= a.d) return;
+    const LaneCoords lc = lane_coords(base, lane, a.d);
+    const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
+    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
+                               groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
+                               lc.wave_ragged, 0u, 0u, a.scales, a.nb, wf, {0.f, 0.f, 0.f, 0.f}};
+    encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
+    if constexpr (FUSE) {
+        float* dst = a.ghat + base + 4 * lane;
+        if (lc.nvalid == 4) {
+            *reinterpret_cast<float4*>(dst) = make_float4(epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (t < lc.nvalid) dst[t] = epi.acc[t];
+        }
+    }
+}
+
+template <int S, int BUCKET>
+static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const Workspace& ws,
+                                    const QuantArgs& a, hipStream_t stream)
+{
+    const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
+    const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
+    if (a.ghat)
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, ws.wq, ws.wf, a);
+    else
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
+                           code.col, code.val, ws.wq, ws.wf, a);
+    return hipGetLastError();
+}
+
+template <int BUCKET>
+static inline hipError_t launch_quantize_band(const float* G, const CodeDev& code, const Workspace& ws,
+                                       const QuantArgs& a, hipStream_t stream)
+{
+    switch (code.band) {
+        case 1: return launch_quantize_s<1, BUCKET>(G, code, ws, a, stream);
+        case 2: return launch_quantize_s<2, BUCKET>(G, code, ws, a, stream);
+        case 3: return launch_quantize_s<3, BUCKET>(G, code, ws, a, stream);
+        case 4: return launch_quantize_s<4, BUCKET>(G, code, ws, a, stream);
+        case 5: return launch_quantize_s<5, BUCKET>(G, code, ws, a, stream);
+        case 6: return launch_quantize_s<6, BUCKET>(G, code, ws, a, stream);
+        case 7: return launch_quantize_s<7, BUCKET>(G, code, ws, a, stream);
+        case 8: return launch_quantize_s<8, BUCKET>(G, code, ws, a, stream);
+        default: return launch_quantize_s<0, BUCKET>(G, code, ws, a, stream);
+    }
+}
+
+// one entry point per instantiation unit
+hipError_t launch_quantize_band0(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
+                                 hipStream_t stream);
+hipError_t launch_quantize_band1(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
+                                 hipStream_t stream);
+hipError_t launch_quantize_band2(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
+                                 hipStream_t stream);
+
+}  // namespace agc
