@@ -308,8 +308,29 @@ class Context:
             arr[i] = t.data_ptr()
         return arr
 
+    def _check_buffers(self, codes, bits, scales=None, ghat=None):
+        """The C ABI sees bare pointers; the binding knows the tensors and refuses buffers that
+        are too small for the geometry the kernels will write or read."""
+        if len(codes) != self.n or len(bits) != self.n:
+            raise AgcError(AGC_ESHAPE, f"expected {self.n} streams and bit-widths")
+        for i, t in enumerate(codes):
+            need = agc_code_bytes(self.d, int(bits[i]))
+            if need and t.numel() * t.element_size() < need:
+                raise AgcError(AGC_ESHAPE, f"codes[{i}] holds {t.numel() * t.element_size()} bytes, "
+                                           f"{need} needed for d={self.d}, bits={int(bits[i])}")
+        if scales is not None and scales.numel() < self.n * self.agc_scales_per_worker():
+            raise AgcError(AGC_ESHAPE, "scales tensor too small")
+        if ghat is not None and ghat.numel() < self.d:
+            raise AgcError(AGC_ESHAPE, "ghat tensor too small")
+
+    def _check_gradients(self, G):
+        if G.dim() != 2 or G.shape[0] < self.k or G.shape[1] < self.d or G.stride(1) != 1:
+            raise AgcError(AGC_ESHAPE, f"G must be a ({self.k}, {self.d}) row-major view, got {tuple(G.shape)}")
+
     def agc_encode_quantize(self, G, bits, seed, step, codes, scales, stream=None, check=True):
         bits = _np(bits, np.uint8)
+        self._check_gradients(G)
+        self._check_buffers(codes, bits, scales)
         st = self.lib.agc_encode_quantize(self.h, C.c_void_p(G.data_ptr()), G.stride(0), _ptr(bits, _u8p),
                                           int(seed), int(step), self._code_ptrs(codes),
                                           C.c_void_p(scales.data_ptr()), _stream_handle(stream))
@@ -319,6 +340,7 @@ class Context:
 
     def agc_decode(self, codes, scales, bits, w, mask, ghat, stream=None, check=True):
         bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
+        self._check_buffers(codes, bits, scales, ghat)
         st = self.lib.agc_decode(self.h, self._code_ptrs(codes), C.c_void_p(scales.data_ptr()),
                                  _ptr(bits, _u8p), _ptr(w, _f32p), _ptr(mask, _u8p),
                                  C.c_void_p(ghat.data_ptr()), _stream_handle(stream))
@@ -328,6 +350,8 @@ class Context:
 
     def agc_decode2(self, codes, scales, bits, w, v, mask, ghat, ghat2, stream=None, check=True):
         bits, w, v, mask = _np(bits, np.uint8), _np(w, np.float32), _np(v, np.float32), _np(mask, np.uint8)
+        self._check_buffers(codes, bits, scales, ghat)
+        self._check_buffers(codes, bits, None, ghat2)
         st = self.lib.agc_decode2(self.h, self._code_ptrs(codes), C.c_void_p(scales.data_ptr()),
                                   _ptr(bits, _u8p), _ptr(w, _f32p), _ptr(v, _f32p), _ptr(mask, _u8p),
                                   C.c_void_p(ghat.data_ptr()), C.c_void_p(ghat2.data_ptr()),
@@ -338,6 +362,8 @@ class Context:
 
     def agc_step(self, G, bits, w, mask, seed, step, codes, scales, ghat, stream=None, check=True):
         bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
+        self._check_gradients(G)
+        self._check_buffers(codes, bits, scales, ghat)
         st = self.lib.agc_step(self.h, C.c_void_p(G.data_ptr()), G.stride(0), _ptr(bits, _u8p), _ptr(w, _f32p),
                                _ptr(mask, _u8p), int(seed), int(step), self._code_ptrs(codes),
                                C.c_void_p(scales.data_ptr()), C.c_void_p(ghat.data_ptr()),
@@ -362,6 +388,12 @@ def agc_ls_workspace_floats(n_rows, n_feat, k_parts):
 
 def agc_ls_partial_gradients(X, y, beta, k_parts, G, resid, workspace, stream=None, check=True):
     """X: (n_rows, n_feat) torch.bfloat16 on the GPU; G: (k_parts, n_feat) float32 view."""
+    n_rows, n_feat = int(X.shape[0]), int(X.shape[1])
+    need_ws = agc_ls_workspace_floats(n_rows, n_feat, k_parts)
+    if (X.dim() != 2 or not X.is_contiguous() or X.element_size() != 2 or y.numel() < n_rows or beta.numel() < n_feat
+            or resid.numel() < n_rows or G.dim() != 2 or G.shape[0] < k_parts or G.shape[1] < n_feat
+            or G.stride(1) != 1 or workspace.numel() < need_ws):
+        raise AgcError(AGC_ESHAPE, "agc_ls_partial_gradients: a tensor is smaller than the shapes require")
     st = load().agc_ls_partial_gradients(C.c_void_p(X.data_ptr()), X.shape[0], X.shape[1],
                                          C.c_void_p(y.data_ptr()), C.c_void_p(beta.data_ptr()), int(k_parts),
                                          C.c_void_p(G.data_ptr()), G.stride(0), C.c_void_p(resid.data_ptr()),

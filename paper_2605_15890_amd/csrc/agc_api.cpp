@@ -208,7 +208,6 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
         if (e == hipSuccess) e = dev_alloc(&c->ws.super_sq, (size_t)c->ws.nsuper * n);
     }
     if (e == hipSuccess) e = dev_alloc(&c->ws.wq, (size_t)n);
-    if (e == hipSuccess) e = dev_alloc(&c->ws.wf, (size_t)n);
     if (e == hipSuccess) e = dev_alloc(&c->ws.wd, (size_t)n);
     if (e == hipSuccess) e = dev_alloc(&c->ws.coef2, (size_t)n);
     if (e != hipSuccess) {
@@ -229,7 +228,6 @@ void agc_destroy(agc_ctx* c)
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
     if (c->ws.wq) (void)hipFree(c->ws.wq);
-    if (c->ws.wf) (void)hipFree(c->ws.wf);
     if (c->ws.wd) (void)hipFree(c->ws.wd);
     if (c->ws.coef2) (void)hipFree(c->ws.coef2);
     if (c->ws.srow) (void)hipFree(c->ws.srow);

@@ -125,6 +125,7 @@ __device__ __forceinline__ double wave_butterfly_add(double v)
 // ---------------------------------------------------------------------------------------
 struct LaneCoords {
     int lane4;         // which float4 of the block the lane loads (clamped into the vector for lanes past d)
+    uint32_t byte_off; // 16 * lane4: the lane's offset inside the block, as the 32-bit part of the address
     int nvalid;        // how many of the lane's four coordinates are < d (0..4)
     bool wave_ragged;  // wave-uniform: some lane of this wave has nvalid < 4
 };
@@ -137,6 +138,7 @@ __device__ __forceinline__ LaneCoords lane_coords(int64_t base, int lane, int64_
     lc.nvalid = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
     const int64_t last4 = (d - 1 - base) >> 2;  // last float4 of the block that holds a coordinate < d
     lc.lane4 = last4 < lane ? (int)last4 : lane;
+    lc.byte_off = 16u * (uint32_t)lc.lane4;
     lc.wave_ragged = __any(lc.nvalid < 4) != 0;
     return lc;
 }
@@ -151,14 +153,14 @@ __device__ __forceinline__ LaneCoords lane_coords(int64_t base, int lane, int64_
 template <bool RAGGED, bool STREAM = false>
 __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const LaneCoords& lc)
 {
-    float4 v;
-    if (STREAM) {
-        typedef float f32x4_t __attribute__((ext_vector_type(4)));
-        const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(row) + lc.lane4);
-        v = make_float4(t.x, t.y, t.z, t.w);
-    } else {
-        v = reinterpret_cast<const float4*>(row)[lc.lane4];
-    }
+    // scalar row pointer + zero-extended 32-bit lane offset: the form the hardware addresses
+    // without any per-lane 64-bit arithmetic
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(1))) char* global_bytes_t;
+    typedef const __attribute__((address_space(1))) f32x4_t* global_f32x4_t;
+    const global_f32x4_t src = (global_f32x4_t)((global_bytes_t)row + lc.byte_off);
+    const f32x4_t t = STREAM ? __builtin_nontemporal_load(src) : *src;
+    float4 v = make_float4(t.x, t.y, t.z, t.w);
     if (RAGGED) {
         if (lc.nvalid < 1) v.x = 0.f;
         if (lc.nvalid < 2) v.y = 0.f;

@@ -17,18 +17,16 @@ struct CodeDev {          // the code matrix B on the device
     int band;             // 0: generic CSR; s>0: cyclic band with s entries per row
 };
 
-// what the quantize pass needs to know about worker i, read with one scalar 16-byte load
+// what the quantize pass needs to know about worker i, read with one scalar 32-byte load
 struct WorkerQ {
     float inv16;          // L_i * 2^16 / scale_i (2^15 / scale_i for a one-bit worker)
     uint32_t bits;
     void* codes;          // packed stream of the worker
-};
-
-// what the fused quantize+decode pass additionally needs: the decode weight of worker i
-// (w_i * scale_i / L_i; with bucket-wise scales w_i / L_i) and whether it arrived
-struct WorkerF {
+    // fused quantize+decode pass only: the decode weight of worker i (w_i * scale_i / L_i; with
+    // bucket-wise scales w_i / L_i) and whether it arrived
     float coef;
     uint32_t arrived;
+    uint32_t pad[2];
 };
 
 // one arrived worker as the decode pass sees it
@@ -44,7 +42,6 @@ struct Workspace {
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
     WorkerQ* wq;          // [n]  written by the scale finalize
-    WorkerF* wf;          // [n]  written with wq when the step runs fused
     WorkerD* wd;          // [n]  arrived workers, compacted, written by the decode prologue
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker

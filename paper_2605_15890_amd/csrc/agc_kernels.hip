@@ -223,11 +223,13 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     if (tid == 0) {
         scales[i] = scale;
         const int b = out.bits[i];
-        ws.wq[i] = WorkerQ{inv16_of(scale, b), (uint32_t)b, out.codes[i]};
+        WorkerQ e{inv16_of(scale, b), (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
         if (sw.fuse) {  // decode weight of one grid unit, as the decode prologue forms it
             const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
-            ws.wf[i] = WorkerF{(float)(((double)sw.w[i] * (double)scale) / L), (uint32_t)sw.arrived[i]};
+            e.coef = (float)(((double)sw.w[i] * (double)scale) / L);
+            e.arrived = (uint32_t)sw.arrived[i];
         }
+        ws.wq[i] = e;
     }
 }
 
@@ -245,17 +247,18 @@ hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
 // =======================================================================================
 // table of the bucket-wise pass: bit-width and stream of every worker (the multiplier is
 // found per block inside the pass)
-__global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams out, StepWeights sw, WorkerQ* wq,
-                                                            WorkerF* wf)
+__global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams out, StepWeights sw, WorkerQ* wq)
 {
     const int i = threadIdx.x;
     if (i >= n) return;
     const int b = out.bits[i];
-    wq[i] = WorkerQ{0.0f, (uint32_t)b, out.codes[i]};
+    WorkerQ e{0.0f, (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
     if (sw.fuse) {
         const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
-        wf[i] = WorkerF{(float)((double)sw.w[i] / L), (uint32_t)sw.arrived[i]};
+        e.coef = (float)((double)sw.w[i] / L);
+        e.arrived = (uint32_t)sw.arrived[i];
     }
+    wq[i] = e;
 }
 
 hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,
@@ -263,7 +266,7 @@ hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int
                                   const Workspace& ws, float* scales, uint64_t seed, uint64_t step, float* ghat,
                                   hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_quant_table, dim3(1), dim3(kWgThreads), 0, stream, n, out, sw, ws.wq, ws.wf);
+    hipLaunchKernelGGL(k_quant_table, dim3(1), dim3(kWgThreads), 0, stream, n, out, sw, ws.wq);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),

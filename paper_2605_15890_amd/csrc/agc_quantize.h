@@ -83,7 +83,6 @@ struct EpiQuant {
     uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
     float* scales;          // bucket-wise scales: n x nb
     int64_t nb;
-    const WorkerF* __restrict__ wf;
     float acc[4];           // fused step: this lane's four coordinates of the estimate
 
     __device__ __forceinline__ float block_multiplier(int i, const float4& f, int b, float& scale)
@@ -163,16 +162,19 @@ struct EpiQuant {
         const float inv = BUCKET == 0 ? q.inv16 : block_multiplier(i, f, b, scale);
         codes4(i, f, inv, b, wa, wb, c, lev);
         if constexpr (FUSE) {
-            const WorkerF wk = wf[i];  // wave-uniform scalar load
-            if (wk.arrived) {
-                const float coef = BUCKET == 0 ? wk.coef : wk.coef * scale;
+            if (q.arrived) {  // wave-uniform
+                const float coef = BUCKET == 0 ? q.coef : q.coef * scale;
                 const float fv[4] = {f.x, f.y, f.z, f.w};
+                if (b >= 2) {  // +-level: the level as a float with the sign bit of f
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float v;
-                    if (b >= 2) v = __uint_as_float(__float_as_uint((float)lev[t]) | (__float_as_uint(fv[t]) & 0x80000000u));
-                    else v = lev[t] ? 1.0f : -1.0f;
-                    acc[t] = fmaf(coef, v, acc[t]);
+                    for (int t = 0; t < 4; ++t) {
+                        const float v = __uint_as_float(__float_as_uint((float)lev[t]) |
+                                                        (__float_as_uint(fv[t]) & 0x80000000u));
+                        acc[t] = fmaf(coef, v, acc[t]);
+                    }
+                } else {  // one-bit worker: +-1
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[t] = fmaf(coef, lev[t] ? 1.0f : -1.0f, acc[t]);
                 }
             }
         }
@@ -220,8 +222,7 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,
-                                                         const WorkerQ* __restrict__ wq,
-                                                         const WorkerF* __restrict__ wf, QuantArgs a)
+                                                         const WorkerQ* __restrict__ wq, QuantArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint32_t lds_stage[kWavesPerWg][kStageWords];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
     const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
     EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
                                groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
-                               lc.wave_ragged, 0u, 0u, a.scales, a.nb, wf, {0.f, 0.f, 0.f, 0.f}};
+                               lc.wave_ragged, 0u, 0u, a.scales, a.nb, {0.f, 0.f, 0.f, 0.f}};
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
@@ -257,10 +258,10 @@ static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const W
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
     if (a.ghat)
         hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
-                           code.col, code.val, ws.wq, ws.wf, a);
+                           code.col, code.val, ws.wq, a);
     else
         hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
-                           code.col, code.val, ws.wq, ws.wf, a);
+                           code.col, code.val, ws.wq, a);
     return hipGetLastError();
 }
 

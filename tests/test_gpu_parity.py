@@ -203,6 +203,16 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.status == api.AGC_ESHAPE
     assert ctx.agc_step(G, bits, w, mask, 1, 1, codes, scales, ghat, check=False) == api.AGC_OK
     torch.cuda.synchronize()
+    # the binding knows the tensors behind the pointers and refuses buffers that are too small
+    small = [c[: c.numel() // 2] for c in codes]
+    for call in (lambda: ctx.agc_step(G, bits, w, mask, 1, 1, small, scales, ghat),
+                 lambda: ctx.agc_step(G, bits + 1, w, mask, 1, 1, codes, scales, ghat),
+                 lambda: ctx.agc_step(G[:, : d - 4], bits, w, mask, 1, 1, codes, scales, ghat),
+                 lambda: ctx.agc_step(G, bits, w, mask, 1, 1, codes, scales, ghat[: d - 1]),
+                 lambda: ctx.agc_decode(small, scales, bits, w, mask, ghat)):
+        with pytest.raises(api.AgcError) as e:
+            call()
+        assert e.value.status == api.AGC_ESHAPE
     ctx.close()
 
 
