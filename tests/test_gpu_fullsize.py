@@ -72,7 +72,16 @@ def test_full_size_sampled_parity(name, scale_mode, nwin):
     ctx.agc_decode(codes, scales, bits, w, np.zeros(n, np.uint8), ghat2)
     torch.cuda.synchronize()
     assert int(torch.count_nonzero(ghat2)) == 0
-    del codes2, scales2, ghat2, G
+    # the stand-alone decode kernel and the two-track decode on the same codes: track one must
+    # repeat the fused step's estimate, track two is checked in the sampled windows below
+    v = api.agc_second_moment_decoder(k, code[0], code[1], code[2], p, np.maximum(bits, 2),
+                                      api.agc_phi_coef_balanced(p, int(bits.sum())), 2.0)
+    ghat_v = torch.empty_like(ghat)
+    ctx.agc_decode2(codes, scales, bits, w, v, mask, ghat2, ghat_v)
+    torch.cuda.synchronize()
+    assert torch.equal(ghat.view(torch.int32), ghat2.view(torch.int32))
+    ghat_v_h = ghat_v.cpu().numpy()
+    del codes2, scales2, ghat2, ghat_v, G
     torch.cuda.empty_cache()
 
     csr = O.Csr(code[0], code[1], code[2], k)
@@ -91,6 +100,8 @@ def test_full_size_sampled_parity(name, scale_mode, nwin):
             flips += int(np.count_nonzero(want != got))
         o_gh = O.decode(streams, o_scales, bits, w, mask, d, m0, m1)
         assert np.array_equal(o_gh.view(np.uint32), ghat_h[m0:m1].view(np.uint32)), (name, m0)
+        o_gv = O.decode(streams, o_scales, bits, v, mask, d, m0, m1)
+        assert np.array_equal(o_gv.view(np.uint32), ghat_v_h[m0:m1].view(np.uint32)), (name, m0, "second track")
     assert flips == 0, flips
     # (3) padding of every stream is zero and the stream has the documented length
     for i in range(n):
@@ -106,4 +117,64 @@ def test_full_size_sampled_parity(name, scale_mode, nwin):
     # on a strided sample of windows is covered by (2); here: the estimate is finite and its
     # norm is of the order of the true gradient sum's
     assert np.isfinite(ghat_h).all()
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,scale_mode,nwin", [
+    ("resnet50", api.AGC_SCALE_MAXABS, 48),
+    ("resnet18", api.AGC_SCALE_L2, 16),
+])
+def test_full_size_bucket_scales_sampled_parity(name, scale_mode, nwin):
+    """The bucket-wise path (one scale per 256 coordinates, single fused pass) at full size:
+    every scale of every worker inside the sampled windows, every code there and the estimate,
+    against the oracle; determinism; stream padding."""
+    import torch
+    cfg = I.CONFIGS[name]
+    p, bits, code, w = _problem(cfg)
+    n, k, d = cfg.n, cfg.k, cfg.d
+    G = I.partial_gradients_torch(cfg, torch.device("cuda:0"))
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=256)
+    ctx.agc_set_code(*code)
+    codes, scales, ghat = ctx.alloc_outputs(bits)
+    for c in codes:
+        c.fill_(0xA5)
+    scales.fill_(float("nan"))
+    step = 5
+    mask = I.arrival_mask(cfg, p, step)
+    ctx.agc_step(G, bits, w, mask, cfg.philox_seed, step, codes, scales, ghat)
+    torch.cuda.synchronize()
+    print(f"[{name} bucket] step done", flush=True)
+    codes2, scales2, ghat2 = ctx.alloc_outputs(bits)
+    ctx.agc_step(G, bits, w, mask, cfg.philox_seed, step, codes2, scales2, ghat2)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(codes, codes2))
+    assert torch.equal(scales.view(torch.int32), scales2.view(torch.int32))
+    assert torch.equal(ghat.view(torch.int32), ghat2.view(torch.int32))
+    del codes2, scales2, ghat2
+    assert not torch.isnan(scales).any()                      # every bucket of every worker was written
+    G_host = G.cpu().numpy()
+    del G
+    streams = [c.cpu().numpy() for c in codes]
+    scales_h = scales.cpu().numpy()
+    ghat_h = ghat.cpu().numpy()
+    csr = O.Csr(code[0], code[1], code[2], k)
+    rng = np.random.default_rng(100 + cfg.index)
+    flips = 0
+    for m0 in _windows(cfg, nwin, rng):
+        m0 -= m0 % 256                                         # windows start on a bucket boundary
+        m1 = min(d, m0 + WINDOW)
+        for i in range(n):
+            want, want_sc = O.codes_bucket_range(G_host, csr, i, int(bits[i]), scale_mode, cfg.philox_seed, step,
+                                                 m0, m1)
+            got_sc = scales_h[i, m0 // 256: m0 // 256 + want_sc.size]
+            assert np.array_equal(want_sc.view(np.uint32), got_sc.view(np.uint32)), (name, i, m0)
+            flips += int(np.count_nonzero(want != O.unpack_range(streams[i], int(bits[i]), m0, m1)))
+        o_gh = O.decode_bucket(streams, scales_h, bits, w, mask, d, m0, m1)
+        assert np.array_equal(o_gh.view(np.uint32), ghat_h[m0:m1].view(np.uint32)), (name, m0)
+    assert flips == 0, flips
+    for i in range(n):
+        b = int(bits[i])
+        assert streams[i].size == O.code_bytes(d, b)
+        first_pad_byte = (d * b + 7) // 8
+        assert not streams[i][first_pad_byte:].any()
     ctx.close()
