@@ -198,10 +198,13 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     c->ws.nseg = (nblocks + 3) / 4;
     c->ws.ngroup = (c->ws.nseg + 63) / 64;
     c->ws.nsuper = (c->ws.ngroup + 63) / 64;
+    c->ws.nblk = nblocks;
+    c->ws.nchunk = (nblocks + agc::kMaxChunkBlocks - 1) / agc::kMaxChunkBlocks;
     if (o.bucket) {
         e = dev_alloc(&c->ws.srow, (size_t)n);  // the scales need no reduction workspace
     } else if (o.scale_mode == AGC_SCALE_MAXABS) {
-        e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nseg * n);
+        e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nblk * n);
+        if (e == hipSuccess) e = dev_alloc(&c->ws.part_max2, (size_t)c->ws.nchunk * n);
     } else {
         e = dev_alloc(&c->ws.part_sq, (size_t)c->ws.nseg * n);
         if (e == hipSuccess) e = dev_alloc(&c->ws.group_sq, (size_t)c->ws.ngroup * n);
@@ -224,6 +227,7 @@ void agc_destroy(agc_ctx* c)
     if (!c) return;
     free_code(c);
     if (c->ws.part_max) (void)hipFree(c->ws.part_max);
+    if (c->ws.part_max2) (void)hipFree(c->ws.part_max2);
     if (c->ws.part_sq) (void)hipFree(c->ws.part_sq);
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);

@@ -37,7 +37,8 @@ struct WorkerD {
 };
 
 struct Workspace {
-    uint32_t* part_max;   // [n][nseg]   per-segment max |f_i| as bit patterns  (max-abs scale)
+    uint32_t* part_max;   // [nblk][n]   per-block max |f_i| as bit patterns    (max-abs scale)
+    uint32_t* part_max2;  // [n][nchunk] the same, reduced over chunks of kMaxChunkBlocks blocks
     double* part_sq;      // [n][nseg]   per-segment sum of squares             (Euclidean scale)
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
@@ -46,7 +47,10 @@ struct Workspace {
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker
     int64_t nseg, ngroup, nsuper;
+    int64_t nblk, nchunk;
 };
+
+constexpr int kMaxChunkBlocks = 512;  // blocks per chunk of the max-abs reduction
 
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];

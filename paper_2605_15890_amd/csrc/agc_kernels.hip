@@ -35,6 +35,9 @@ struct ScaleArgs {
     double* part_sq;
 };
 
+// the same 32-bit word seen as device memory (store without address-space checks)
+typedef __attribute__((address_space(1))) uint32_t global_word;
+
 // epilogue for the largest-magnitude scale: exact and order-free
 struct EpiMaxAbs {
     uint32_t* acc;  // this wave's LDS slice [n], bit patterns of non-negative floats
@@ -64,9 +67,12 @@ struct EpiSumSq {
     }
 };
 
-// One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it; the
-// four block values of every worker meet in LDS and are combined in block order (level 2 of
-// the tree), which keeps the result independent of how the waves were scheduled.
+// One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it.
+// Euclidean scale: the four block values of every worker meet in LDS and are combined in block
+// order (level 2 of the tree), which keeps the result independent of how the waves were
+// scheduled.  Max-abs scale: the maximum is order-free, so every wave stores its own block's
+// values ([block][worker], one coalesced store) and leaves without waiting for the other
+// waves - the barrier alone cost 4 % of the pass.
 template <int S, int MODE>
 __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restrict__ G,
                                                            const int* __restrict__ row_ptr,
@@ -99,6 +105,14 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
             else accu[i] = 0u;
         }
     }
+    if (MODE == 1) {
+        if (base < a.d) {
+            const int64_t blk = seg * kSegBlocks + wave;
+            global_word* dst = (global_word*)a.part_max + blk * a.n;
+            for (int i = lane; i < a.n; i += kWave) dst[i] = accu[i];  // written by this wave's lane 0
+        }
+        return;
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < a.n; i += kWgThreads) {
         if (MODE == 0) {
@@ -106,12 +120,39 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
 #pragma unroll
             for (int w = 0; w < kWavesPerWg; ++w) sum = sum + lds_acc[w][i];
             a.part_sq[(int64_t)i * a.nseg + seg] = sum;
-        } else {
-            uint32_t m = 0u;
-#pragma unroll
-            for (int w = 0; w < kWavesPerWg; ++w) m = max(m, reinterpret_cast<uint32_t*>(lds_acc[w])[i]);
-            a.part_max[(int64_t)i * a.nseg + seg] = m;
         }
+    }
+}
+
+// max-abs scale, first reduction: [block][worker] -> [worker][chunk of kMaxChunkBlocks blocks].
+// grid (chunks, ceil(n/64)); lane l of every wave follows worker 64*blockIdx.y + l through the
+// chunk's rows (one coalesced 4n-byte row per step), the four waves take every fourth row.
+__global__ __launch_bounds__(kWgThreads) void k_scale_reduce_max(int n, Workspace ws)
+{
+    __shared__ uint32_t red[kWavesPerWg][kWave];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int i = (int)blockIdx.y * kWave + lane;
+    const int64_t b0 = (int64_t)blockIdx.x * kMaxChunkBlocks;
+    const int64_t b1 = b0 + kMaxChunkBlocks < ws.nblk ? b0 + kMaxChunkBlocks : ws.nblk;
+    uint32_t m = 0u;
+    if (i < n) {
+        const uint32_t* col = ws.part_max + i;
+        for (int64_t blk = b0 + wave; blk < b1; blk += 8 * kWavesPerWg) {
+            uint32_t v[8];  // eight independent loads in flight per lane
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t bb = blk + (int64_t)u * kWavesPerWg;
+                v[u] = bb < b1 ? col[bb * n] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m = max(m, v[u]);
+        }
+    }
+    red[wave][lane] = m;
+    __syncthreads();
+    if (wave == 0 && i < n) {
+        m = max(max(red[0][lane], red[1][lane]), max(red[2][lane], red[3][lane]));
+        ws.part_max2[(int64_t)i * ws.nchunk + blockIdx.x] = m;
     }
 }
 
@@ -168,13 +209,13 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     float scale;
     if (MODE == 1) {
         uint32_t m = 0u;
-        const uint32_t* part = ws.part_max + (int64_t)i * ws.nseg;
-        for (int64_t s0 = tid; s0 < ws.nseg; s0 += 8 * kWgThreads) {
+        const uint32_t* part = ws.part_max2 + (int64_t)i * ws.nchunk;
+        for (int64_t s0 = tid; s0 < ws.nchunk; s0 += 8 * kWgThreads) {
             uint32_t v[8];  // eight independent loads in flight per lane
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int64_t s = s0 + (int64_t)u * kWgThreads;
-                v[u] = s < ws.nseg ? part[s] : 0u;
+                v[u] = s < ws.nchunk ? part[s] : 0u;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) m = max(m, v[u]);
@@ -236,8 +277,15 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
 hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
-    if (scale_mode == 0) hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
-    else hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
+    if (scale_mode == 0) {
+        hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
+    } else {
+        hipLaunchKernelGGL(k_scale_reduce_max, dim3((unsigned)ws.nchunk, (unsigned)((n + kWave - 1) / kWave)),
+                           dim3(kWgThreads), 0, stream, n, ws);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
+    }
     return hipGetLastError();
 }
 
