@@ -154,8 +154,9 @@ def main():
                     help="also run one plain 1 GiB copy kernel (reference for the traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (the design for "
-              "sharding along d is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path (it would shard the "
+              "coordinate axis d, exchanging only the per-worker scale partials). Run with --gpus 1.",
+              file=sys.stderr)
         sys.exit(2)
 
     if args.workload == "lsq":

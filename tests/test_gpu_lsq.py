@@ -6,6 +6,7 @@ import pytest
 
 from oracle import agc_oracle as O
 from oracle import lsq as LS
+from oracle import optim as P
 from paper_2605_15890_amd import api
 from paper_2605_15890_amd import inputs as I
 
@@ -74,7 +75,7 @@ def test_gd_update():
     bd, gd = torch.from_numpy(b).cuda(), torch.from_numpy(g).cuda()
     api.agc_gd_update(bd, gd, 0.125)
     torch.cuda.synchronize()
-    want = (b.astype(np.float64) - 0.125 * g.astype(np.float64)).astype(np.float32)   # single rounding (fma)
+    want = P.gd_update(b, g, 0.125).astype(np.float32)                                 # single rounding (fma)
     assert np.array_equal(bd.cpu().numpy(), want)
 
 
@@ -120,7 +121,7 @@ def test_end_to_end_loop_follows_the_oracle_loop():
         G_o, r_o = LS.partial_gradients(Xb, y, beta_o, k)
         loss_o.append(0.5 * float(r_o @ r_o))
         _, _, gh_o = O.step(G_o.astype(np.float32), csr, bits, w, mask, seed, t, O.SCALE_MAXABS)
-        beta_o = (beta_o.astype(np.float64) - float(lr) * gh_o.astype(np.float64)).astype(np.float32)
+        beta_o = P.gd_update(beta_o, gh_o, float(lr)).astype(np.float32)
     torch.cuda.synchronize()
     ctx.close()
     loss_d, loss_o = np.array(loss_d), np.array(loss_o)

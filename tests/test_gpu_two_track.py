@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import agc_oracle as O
+from oracle import optim as P
 from paper_2605_15890_amd import api
 from paper_2605_15890_amd import inputs as I
 
@@ -103,9 +104,8 @@ def test_adam_update_matches_fp64():
         g = rng.standard_normal(d).astype(np.float32)
         h = (g + 0.1 * rng.standard_normal(d)).astype(np.float32)
         api.agc_adam_update(bd, m1d, m2d, torch.from_numpy(g).cuda(), torch.from_numpy(h).cuda(), lr, b1, b2, eps, t)
-        a64 = b1f * a64 + (1 - b1f) * g
-        c64 = b2f * c64 + (1 - b2f) * h.astype(np.float64) ** 2
-        b64 = b64 - float(np.float32(lr)) * (a64 / (1 - b1f ** t)) / (np.sqrt(c64 / (1 - b2f ** t)) + float(np.float32(eps)))
+        b64, a64, c64 = P.adam_update(b64, a64, c64, g, h, float(np.float32(lr)), b1f, b2f,
+                                      float(np.float32(eps)), t)
     torch.cuda.synchronize()
     assert np.allclose(m1d.cpu().numpy(), a64, rtol=1e-5, atol=1e-7)
     assert np.allclose(m2d.cpu().numpy(), c64, rtol=1e-5, atol=1e-9)
