@@ -42,6 +42,20 @@ def build_problem(cfg, api, code_kind):
     return p, bits, (row_ptr, col, val), w
 
 
+def stored_valu(tag, kernel):
+    """Vector-ALU lane-operations per launch of `kernel` (rocprofv3 --pmc SQ_INSTS_VALU x 64),
+    recorded in the same profiles/traffic_<tag>.txt; None when absent."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{tag}.txt")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        for line in fh:
+            f = line.split()
+            if len(f) >= 3 and f[0] == "valu_lane_ops_per_launch" and f[1] == kernel:
+                return float(f[2])
+    return None
+
+
 def stored_traffic(tag, kernel):
     """HBM bytes per launch of `kernel` as measured offline with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE (scaled by the calibration copy) and recorded in profiles/traffic_<tag>.txt;
@@ -240,6 +254,12 @@ def main():
         "step_alg_bytes": step_alg_bytes,
         "step_hbm_frac": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
+    valu_ops = stored_valu(tag, dominant)
+    if valu_ops:   # the kernel is co-bound by plain vector ALU work: say how close to that peak it runs
+        roofline["valu"] = {"lane_ops_per_launch": valu_ops,
+                            "achieved_Tlaneops": round(valu_ops / dom_avg_s / 1e12, 2),
+                            "peak_Tlaneops": round(VALU_PEAK_GLANEOPS / 1e3, 2),
+                            "frac": round(valu_ops / dom_avg_s / 1e9 / VALU_PEAK_GLANEOPS, 4)}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
