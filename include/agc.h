@@ -95,7 +95,10 @@ void agc_destroy(agc_ctx *ctx);
  * give identical bits. */
 agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col, const float *val);
 
-/* 0 = generic gather path, s > 0 = cyclic-band path with replication s; < 0 = no code set. */
+/* 0 = generic gather path; 1..8 = cyclic-band path with replication s; 102, 104, 108 = monotone-
+ * interval path (every row a run of at most 2, 4, 8 consecutive ascending columns whose ends never
+ * decrease from one worker to the next - the shape agc_build_code produces); < 0 = no code set.
+ * All paths give identical bits; the last two read every element of G once per pass. */
 int agc_code_path(const agc_ctx *ctx);
 
 /* Bytes of one worker's packed stream: ceil(d/128) * 16 * bits (Sec. II-B: the payload is

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <algorithm>
 #include <cmath>
 #include <vector>
 
@@ -266,6 +267,25 @@ agc_status agc_set_code(agc_ctx* c, const int32_t* row_ptr, const int32_t* col, 
         }
         if (ok) band = s;
     }
+    // monotone intervals (the shape of the paper's sparse construction): every row stores a run of
+    // consecutive ascending columns, at most 8 of them, and neither end of the run decreases from
+    // one worker to the next.  Stored as -W, W the window (2, 4 or 8) that holds the longest run.
+    if (band == 0 && nnz > 0) {
+        bool ok = true;
+        int longest = 0, prev_lo = 0, prev_hi = 0;
+        for (int i = 0; ok && i < c->n; ++i) {
+            const int e0 = row_ptr[i], len = row_ptr[i + 1] - e0;
+            ok = len >= 1 && len <= 8;
+            for (int u = 1; ok && u < len; ++u) ok = col[e0 + u] == col[e0] + u;
+            if (!ok) break;
+            const int lo = col[e0], hi = lo + len - 1;
+            if (i > 0) ok = lo >= prev_lo && hi >= prev_hi;
+            prev_lo = lo;
+            prev_hi = hi;
+            longest = std::max(longest, len);
+        }
+        if (ok) band = -(longest <= 2 ? 2 : (longest <= 4 ? 4 : 8));
+    }
     free_code(c);
     hipError_t e = dev_alloc(&c->d_row_ptr, (size_t)c->n + 1);
     if (e == hipSuccess) e = dev_alloc(&c->d_col, (size_t)(nnz > 0 ? nnz : 1));
@@ -286,7 +306,8 @@ agc_status agc_set_code(agc_ctx* c, const int32_t* row_ptr, const int32_t* col, 
 int agc_code_path(const agc_ctx* c)
 {
     if (!c || !c->has_code) return -1;
-    return c->opts.force_generic ? 0 : c->band;
+    if (c->opts.force_generic) return 0;
+    return c->band >= 0 ? c->band : 100 - c->band;
 }
 
 }  // extern "C"

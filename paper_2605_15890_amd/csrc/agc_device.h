@@ -339,15 +339,91 @@ __device__ __forceinline__ void encode_gather(const float* __restrict__ G, int64
     }
 }
 
-// One block of 256 coordinates for all workers.  The register ring serves whole blocks of a
-// cyclic-band code; the one block that straddles d (and any other code) goes through the
-// gather driver, which masks the coordinates past the end.  Both give identical bits.
+// ---------------------------------------------------------------------------------------
+// Encode driver 3: monotone intervals.  Every worker stores a run of consecutive columns
+// lo_i .. lo_i+len_i-1 (ascending, len_i <= W) and neither lo_i nor lo_i+len_i-1 decreases with i
+// - the shape of the paper's sparse construction (Sec. III-A: contiguous allocation segments on
+// the partition axis).  Rows stream once through the same register ring as the cyclic band; a
+// worker is formed when row lo_i + W - 1 arrives, so that row lo_i + u sits at a ring position
+// that is known at compile time; entries u >= len_i are skipped by wave-uniform branches (not
+// multiplied by zero: the sum must have exactly the stored terms).  Several workers, or none, may
+// be anchored at the same row.
+// ---------------------------------------------------------------------------------------
+template <int W, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void window_step(float4 (&ring)[RingShape<W>::R], const float*& next_row,
+                                            int64_t ldg, int n, int k, const CsrView& B,
+                                            const LaneCoords& lc, int j0, int& i, Epi& epi)
+{
+    constexpr int P = RingShape<W>::P;
+    constexpr int R = RingShape<W>::R;
+    const int j = j0 + r;
+    if (STEADY || j + P < k) {  // prefetch the row that arrives P steps from now
+        ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
+        next_row += (j + P + 1 < k) ? ldg : 0;
+    }
+    const int lo = j - (W - 1);
+    while (i < n) {
+        const int e0 = B.row_ptr[i];
+        if (B.col[e0] != lo) break;
+        const int len = B.row_ptr[i + 1] - e0;
+        float4 f = mul4(B.val[e0], ring[(r + R - (W - 1)) % R]);
+#pragma unroll
+        for (int u = 1; u < W; ++u)
+            if (u < len) f = fma4(B.val[e0 + u], ring[(r + R - (W - 1) + u) % R], f);
+        epi.worker_any(i, f);
+        ++i;
+    }
+}
+
+template <int W, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void window_round(float4 (&ring)[RingShape<W>::R], const float*& next_row,
+                                             int64_t ldg, int n, int k, const CsrView& B,
+                                             const LaneCoords& lc, int j0, int& i, Epi& epi,
+                                             std::integer_sequence<int, Rs...>)
+{
+    (window_step<W, Rs, STEADY>(ring, next_row, ldg, n, k, B, lc, j0, i, epi), ...);
+}
+
+template <int W, class Epi>
+__device__ __forceinline__ void encode_window(const float* __restrict__ G, int64_t ldg, int n, int k,
+                                              const CsrView& B, const LaneCoords& lc, Epi& epi)
+{
+    constexpr int P = RingShape<W>::P;
+    constexpr int R = RingShape<W>::R;
+    constexpr auto seq = std::make_integer_sequence<int, R>{};
+    float4 ring[R];
+    const float* next_row = G;
+#pragma unroll
+    for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int r = 0; r < P; ++r) {
+        if (r < k) {
+            ring[r] = load_row4<false, true>(next_row, lc);
+            next_row += (r + 1 < k) ? ldg : 0;
+        }
+    }
+    int i = 0;
+    int j0 = 0;
+    const int steps = k + W - 1;  // the last worker may be anchored at row k-1
+    for (; j0 + R - 1 + P < k; j0 += R)  // every prefetch of the round exists
+        window_round<W, true>(ring, next_row, ldg, n, k, B, lc, j0, i, epi, seq);
+    for (; j0 < steps; j0 += R)
+        window_round<W, false>(ring, next_row, ldg, n, k, B, lc, j0, i, epi, seq);
+}
+
+// One block of 256 coordinates for all workers.  S > 0: cyclic band of width S; S < 0: monotone
+// intervals of at most -S columns; S == 0: any code.  The register ring serves whole blocks; the
+// one block that straddles d (and any other code) goes through the gather driver, which masks
+// the coordinates past the end.  All give identical bits.
 template <int S, class Epi>
 __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_t ldg, int n, int k,
                                              const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     if constexpr (S > 0) {
         if (!lc.wave_ragged) encode_ring<S>(G, ldg, k, B.val, lc, epi);
+        else encode_gather<true>(G, ldg, n, B, lc, epi);
+    } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
+        if (!lc.wave_ragged) encode_window<-S>(G, ldg, n, k, B, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);

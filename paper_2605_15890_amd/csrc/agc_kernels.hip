@@ -49,6 +49,7 @@ struct EpiMaxAbs {
         const uint32_t m = wave_max_nonneg_bits(a);
         if (lane == 0) acc[i] = m;
     }
+    __device__ __forceinline__ void worker_any(int i, const float4& f) { worker<true>(i, f); }
 };
 
 // epilogue for the Euclidean scale: levels 0 and 1 of the binary64 summation tree (lane value
@@ -65,6 +66,7 @@ struct EpiSumSq {
         const double q = wave_butterfly_add(s01 + s23);
         if (lane == 0) acc[i] = q;
     }
+    __device__ __forceinline__ void worker_any(int i, const float4& f) { worker<true>(i, f); }
 };
 
 // One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it.
@@ -184,6 +186,9 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
         case 6: return launch_scale_pass_s<6>(G, code, a, scale_mode, stream);
         case 7: return launch_scale_pass_s<7>(G, code, a, scale_mode, stream);
         case 8: return launch_scale_pass_s<8>(G, code, a, scale_mode, stream);
+        case -2: return launch_scale_pass_s<-2>(G, code, a, scale_mode, stream);
+        case -4: return launch_scale_pass_s<-4>(G, code, a, scale_mode, stream);
+        case -8: return launch_scale_pass_s<-8>(G, code, a, scale_mode, stream);
         default: return launch_scale_pass_s<0>(G, code, a, scale_mode, stream);
     }
 }

@@ -323,3 +323,68 @@ def test_fused_step_equals_two_pass_step(bucket):
                 assert all(torch.equal(a, b) for a, b in zip(c0, c1))
                 assert torch.equal(s0.view(torch.int32), s1.view(torch.int32))
                 assert torch.equal(g0.view(torch.int32), g1.view(torch.int32))
+
+
+def _monotone_code(rng, n, k, max_len):
+    """Random code of the monotone-interval shape: runs of consecutive columns whose two ends
+    never decrease; several workers may start at the same column, columns may be skipped."""
+    row_ptr, col, val = [0], [], []
+    lo = hi = 0
+    for i in range(n):
+        lo = min(k - 1, max(lo, hi - int(rng.integers(0, 2))) + (int(rng.integers(0, 2)) if i else 0))
+        length = int(rng.integers(1, max_len + 1))
+        new_hi = min(k - 1, max(hi, lo + length - 1))
+        if new_hi - lo + 1 > max_len:
+            lo = new_hi - max_len + 1
+        hi = new_hi
+        cols = list(range(lo, hi + 1))
+        col += cols
+        val += list(rng.uniform(-1.0, 1.0, len(cols)).astype(np.float32))
+        row_ptr.append(len(col))
+    return np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(val, np.float32)
+
+
+@pytest.mark.parametrize("n,k,max_len,d", [(3, 1, 1, 300), (5, 9, 2, 1000), (9, 5, 2, 4097), (33, 20, 4, 2048),
+                                           (40, 64, 4, 70001), (64, 64, 8, 5000), (200, 17, 8, 1025), (17, 200, 8, 3000)])
+def test_monotone_interval_codes_take_the_window_path(n, k, max_len, d):
+    rng = np.random.default_rng(n * 1000 + k)
+    row_ptr, col, val = _monotone_code(rng, n, k, max_len)
+    longest = int(np.diff(row_ptr).max())
+    want_path = 100 + (2 if longest <= 2 else 4 if longest <= 4 else 8)
+    bits = rng.integers(1, 17, n).astype(np.uint8)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = (rng.random(n) < 0.7).astype(np.uint8)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    Gd = to_device(G)
+    for scale_mode in MODES:
+        out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 5, 9, scale_mode, allow_1bit=True,
+                      expect_path=want_path)
+        compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 5, 9, scale_mode, out,
+                            tag=f"window n={n} k={k} len={longest} mode={scale_mode}")
+
+
+@pytest.mark.parametrize("name", ["n16_d1m", "resnet18"])
+def test_paper_interval_code_on_named_configs(name):
+    """The sparse construction of Sec. III-A (contiguous allocation segments) for the named
+    configurations, first 2^16+5 coordinates: window path, oracle bits, and the same bits as the
+    generic path."""
+    cfg = I.CONFIGS[name]
+    d = (1 << 16) + 5
+    p = I.straggler_probs(cfg)
+    bits = I.random_bits(cfg)
+    if bits is None:
+        z_tot = cfg.bits_law[1] * cfg.n
+        bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    row_ptr, col, val, w = api.agc_build_code(cfg.n, cfg.k, p, np.maximum(bits, 2), pc)
+    G = I.partial_gradients_numpy(cfg, d=d)
+    Gd = to_device(G)
+    mask = I.arrival_mask(cfg, p, 2)
+    outs = []
+    for force_generic in (False, True):
+        out = run_hip(Gd, cfg.n, cfg.k, d, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 2,
+                      api.AGC_SCALE_MAXABS, allow_1bit=cfg.allow_1bit, force_generic=force_generic)
+        compare_with_oracle(G, cfg.k, row_ptr, col, val, bits, w, mask, cfg.philox_seed, 2, api.AGC_SCALE_MAXABS,
+                            out, tag=f"{name} interval generic={force_generic}")
+        outs.append(out)
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0][0], outs[1][0]))
