@@ -29,7 +29,7 @@ def _rel(a, b):
 
 
 @pytest.mark.parametrize("n_rows,n_feat,k", [(1024, 128, 4), (4096, 512, 8), (3 * 16 * 7, 1280, 3),
-                                             (8192, 4096, 32), (2048, 8192, 2)])
+                                             (8192, 4096, 32), (2048, 8192, 2), (512, 4224, 4), (256, 384, 1)])
 def test_partial_gradients_match_fp64(n_rows, n_feat, k):
     import torch
     Xb, y, w_star, X, y_d = _device_problem(n_rows, n_feat)
