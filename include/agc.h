@@ -18,7 +18,9 @@
  *     HIP stream (a hipStream_t passed as void*, NULL = the default stream) and return
  *     without waiting and without any host<->device copy: the small host arrays (bits, w,
  *     mask, code pointers) travel as kernel arguments;
- *   - NaN or infinity in G is outside the contract (no check on the hot path).
+ *   - NaN or infinity in G is outside the contract (no check on the hot path);
+ *   - a context's workspace and tables are shared by all its calls: calls on one context must be
+ *     ordered (one stream, or events between streams); concurrent streams need one context each.
  *
  * Arithmetic fixed by this library (the paper leaves these open; the CPU oracle in
  * oracle/ takes the same readings):
@@ -30,7 +32,15 @@
  *              (see agc_encode_quantize);
  *   payload    per worker a little-endian bit stream, code m in bits [m*b, (m+1)*b),
  *              zero-padded to whole groups of 128 codes (agc_code_bytes);
- *   decode     binary32, arrived workers in ascending order, one fused multiply-add each.
+ *   decode     binary32, arrived workers in ascending order, one fused multiply-add each;
+ *   bucket-wise scales (agc_opts.bucket = 256; Sec. II-B names the extension, the arithmetic is
+ *              this library's): bucket u = coordinates [256u, 256u+256) below d; scale_iu = largest
+ *              magnitude of f_i in the bucket, or (float)sqrt of the bucket's binary64 sum of squares
+ *              (the two lowest levels of the tree); multiplier = L_i*2^16 / scale_iu (2^15 / scale_iu
+ *              for one bit) as ONE correctly rounded binary32 division, 0 for an empty or overflowing
+ *              bucket; rounding rule, draws, codes and payload as above; decode weight =
+ *              (float)((double)w_i / L_i) * scale_iu, one binary32 product; scales_dev is n x
+ *              ceil(d/256), row-major.
  */
 #ifndef AGC_H
 #define AGC_H
