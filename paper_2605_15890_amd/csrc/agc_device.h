@@ -309,6 +309,25 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
 // Encode driver 2: any CSR code.  Each worker gathers its rows straight from memory; rows
 // shared by neighbouring workers are served by the caches.
 // ---------------------------------------------------------------------------------------
+// Wave-uniform read of a small read-only table (code structure, per-worker records).  Tagging the
+// address as constant memory keeps the read on the scalar path even in a kernel that also stores:
+// otherwise the compiler must assume its own stores may have changed the table, reads it with a
+// vector load and waits for every outstanding load and store.  Nothing writes these tables while
+// a kernel that reads them runs.
+template <class T>
+__device__ __forceinline__ T load_uniform(const T* p)
+{
+    static_assert(sizeof(T) % 4 == 0, "whole dwords");
+    constexpr int N = sizeof(T) / 4;
+    const __attribute__((address_space(4))) uint32_t* q = (const __attribute__((address_space(4))) uint32_t*)p;
+    uint32_t w[N];
+#pragma unroll
+    for (int t = 0; t < N; ++t) w[t] = q[t];
+    T out;
+    __builtin_memcpy(&out, w, sizeof(T));
+    return out;
+}
+
 struct CsrView {
     const int* __restrict__ row_ptr;
     const int* __restrict__ col;
@@ -411,6 +430,66 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
         window_round<W, false>(ring, next_row, ldg, n, k, B, lc, j0, i, epi, seq);
 }
 
+// The same driver for epilogues that store inside the worker loop (the quantize pass).  Stores
+// and loads share one outstanding-operation counter on this hardware, so behind a loop of unknown
+// length the compiler can only wait for everything; a rolling prefetch would be drained at every
+// row.  Here the rows arrive in batches of BT: one batch is requested, waited for as a whole, and
+// then its BT row steps run without further loads.  The ring holds two batches (the previous one
+// supplies the up to W-1 older rows a worker may need), so all positions stay compile-time.
+template <int W>
+struct BatchShape {
+    static constexpr int BT = W >= 4 ? W : 4;  // rows per batch, >= W - 1
+    static constexpr int R = 2 * BT;
+};
+
+template <int W, int HALF, class Epi>
+__device__ __forceinline__ void window_batch(float4 (&ring)[BatchShape<W>::R], const float* __restrict__ G,
+                                             int64_t ldg, int n, int k, const CsrView& B,
+                                             const LaneCoords& lc, int row0, int& i, Epi& epi)
+{
+    constexpr int BT = BatchShape<W>::BT;
+    constexpr int R = BatchShape<W>::R;
+    if (row0 < k) {  // one straight run of loads; a batch that straddles the end repeats row k-1
+#pragma unroll
+        for (int r = 0; r < BT; ++r) {
+            const int row = row0 + r < k ? row0 + r : k - 1;
+            ring[HALF * BT + r] = load_row4<false, true>(G + (int64_t)row * ldg, lc);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < BT; ++r) {
+        const int lo = row0 + r - (W - 1);
+        while (i < n) {
+            const int e0 = load_uniform(B.row_ptr + i);
+            if (load_uniform(B.col + e0) != lo) break;
+            const int len = load_uniform(B.row_ptr + i + 1) - e0;
+            float4 f = mul4(load_uniform(B.val + e0), ring[(HALF * BT + r + R - (W - 1)) % R]);
+#pragma unroll
+            for (int u = 1; u < W; ++u)
+                if (u < len) f = fma4(load_uniform(B.val + e0 + u), ring[(HALF * BT + r + R - (W - 1) + u) % R], f);
+            epi.worker_any(i, f);
+            ++i;
+        }
+    }
+}
+
+template <int W, class Epi>
+__device__ __forceinline__ void encode_window_batched(const float* __restrict__ G, int64_t ldg, int n, int k,
+                                                      const CsrView& B, const LaneCoords& lc, Epi& epi)
+{
+    constexpr int BT = BatchShape<W>::BT;
+    constexpr int R = BatchShape<W>::R;
+    float4 ring[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    int i = 0;
+    const int steps = k + W - 1;  // the last worker may be anchored at row k-1
+    for (int row0 = 0; row0 < steps; row0 += R) {
+        window_batch<W, 0>(ring, G, ldg, n, k, B, lc, row0, i, epi);
+        if (row0 + BT < steps) window_batch<W, 1>(ring, G, ldg, n, k, B, lc, row0 + BT, i, epi);
+    }
+}
+
 // One block of 256 coordinates for all workers.  S > 0: cyclic band of width S; S < 0: monotone
 // intervals of at most -S columns; S == 0: any code.  The register ring serves whole blocks; the
 // one block that straddles d (and any other code) goes through the gather driver, which masks
@@ -423,8 +502,9 @@ __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_
         if (!lc.wave_ragged) encode_ring<S>(G, ldg, k, B.val, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);
     } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
-        if (!lc.wave_ragged) encode_window<-S>(G, ldg, n, k, B, lc, epi);
-        else encode_gather<true>(G, ldg, n, B, lc, epi);
+        if (lc.wave_ragged) encode_gather<true>(G, ldg, n, B, lc, epi);
+        else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, n, k, B, lc, epi);
+        else encode_window<-S>(G, ldg, n, k, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);

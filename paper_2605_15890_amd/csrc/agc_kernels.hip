@@ -40,6 +40,7 @@ typedef __attribute__((address_space(1))) uint32_t global_word;
 
 // epilogue for the largest-magnitude scale: exact and order-free
 struct EpiMaxAbs {
+    static constexpr bool kStoresPerWorker = false;
     uint32_t* acc;  // this wave's LDS slice [n], bit patterns of non-negative floats
     int lane;
     template <bool EVEN>
@@ -55,6 +56,7 @@ struct EpiMaxAbs {
 // epilogue for the Euclidean scale: levels 0 and 1 of the binary64 summation tree (lane value
 // (x0^2+x1^2)+(x2^2+x3^2); exchange-add across the 64 lanes)
 struct EpiSumSq {
+    static constexpr bool kStoresPerWorker = false;
     double* acc;  // this wave's LDS slice [n]
     int lane;
     template <bool EVEN>

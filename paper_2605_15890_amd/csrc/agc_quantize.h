@@ -71,6 +71,7 @@ __device__ __forceinline__ void wave_lds_fence()
 // arithmetic of the stand-alone decode kernel, so both give the same bits.
 template <int BUCKET, bool FUSE>
 struct EpiQuant {
+    static constexpr bool kStoresPerWorker = true;  // the payload leaves inside the worker loop
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
     uint32_t* stage;     // this wave's LDS staging words, all zero between workers
@@ -177,7 +178,7 @@ struct EpiQuant {
 
     __device__ __forceinline__ void finish(int i, const float4& f, uint32_t wa, uint32_t wb)
     {
-        const WorkerQ q = wq[i];  // wave-uniform: one scalar 16-byte load
+        const WorkerQ q = load_uniform(wq + i);  // wave-uniform scalar read
         const int b = (int)q.bits;
         uint32_t c[4], lev[4];
         float scale = 0.f;
@@ -300,11 +301,9 @@ static inline hipError_t launch_quantize_band(const float* G, const CodeDev& cod
         case 6: return launch_quantize_s<6, BUCKET>(G, code, ws, a, stream);
         case 7: return launch_quantize_s<7, BUCKET>(G, code, ws, a, stream);
         case 8: return launch_quantize_s<8, BUCKET>(G, code, ws, a, stream);
-        // monotone-interval codes (band < 0) take the gather driver here: this pass stores inside
-        // the per-row worker loop, and on this hardware stores share the counter that tracks
-        // outstanding loads, so behind a loop of unknown length the compiler can only wait for all
-        // of them - the window driver then loses its prefetch (measured 3.4 ms against 1.9 ms).
-        // The scale pass, which stores nothing in that loop, does use the window driver.
+        case -2: return launch_quantize_s<-2, BUCKET>(G, code, ws, a, stream);
+        case -4: return launch_quantize_s<-4, BUCKET>(G, code, ws, a, stream);
+        case -8: return launch_quantize_s<-8, BUCKET>(G, code, ws, a, stream);
         default: return launch_quantize_s<0, BUCKET>(G, code, ws, a, stream);
     }
 }
