@@ -34,6 +34,7 @@ struct agc_ctx {
     int* d_row_ptr = nullptr;
     int* d_col = nullptr;
     float* d_val = nullptr;
+    agc::WindowRec* d_win = nullptr;   // monotone-interval codes only
     int band = 0;
     // workspace
     agc::Workspace ws{};
@@ -74,6 +75,8 @@ void free_code(agc_ctx* c)
     if (c->d_row_ptr) (void)hipFree(c->d_row_ptr);
     if (c->d_col) (void)hipFree(c->d_col);
     if (c->d_val) (void)hipFree(c->d_val);
+    if (c->d_win) (void)hipFree(c->d_win);
+    c->d_win = nullptr;
     c->d_row_ptr = nullptr;
     c->d_col = nullptr;
     c->d_val = nullptr;
@@ -148,7 +151,7 @@ agc_status check_streams(agc_ctx* c, void* const* codes)
 
 agc::CodeDev code_dev(const agc_ctx* c)
 {
-    return agc::CodeDev{c->d_row_ptr, c->d_col, c->d_val, c->opts.force_generic ? 0 : c->band};
+    return agc::CodeDev{c->d_row_ptr, c->d_col, c->d_val, c->opts.force_generic ? 0 : c->band, c->d_win};
 }
 
 }  // namespace
@@ -293,6 +296,23 @@ agc_status agc_set_code(agc_ctx* c, const int32_t* row_ptr, const int32_t* col, 
     if (e == hipSuccess) e = hipMemcpy(c->d_row_ptr, row_ptr, sizeof(int) * ((size_t)c->n + 1), hipMemcpyHostToDevice);
     if (e == hipSuccess && nnz > 0) e = hipMemcpy(c->d_col, col, sizeof(int) * (size_t)nnz, hipMemcpyHostToDevice);
     if (e == hipSuccess && nnz > 0) e = hipMemcpy(c->d_val, val, sizeof(float) * (size_t)nnz, hipMemcpyHostToDevice);
+    if (e == hipSuccess && band < 0) {  // one record per row plus the sentinel
+        std::vector<agc::WindowRec> win((size_t)c->n + 1);
+        for (int i = 0; i <= c->n; ++i) {
+            agc::WindowRec r{};
+            if (i < c->n) {
+                const int e0 = row_ptr[i];
+                r.lo = col[e0];
+                r.len = row_ptr[i + 1] - e0;
+                for (int u = 0; u < r.len; ++u) r.val[u] = val[e0 + u];
+            } else {
+                r.lo = INT32_MAX;
+            }
+            win[(size_t)i] = r;
+        }
+        e = dev_alloc(&c->d_win, win.size());
+        if (e == hipSuccess) e = hipMemcpy(c->d_win, win.data(), sizeof(agc::WindowRec) * win.size(), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         free_code(c);
         return hip_fail(c, e, "uploading the code matrix");

@@ -12,6 +12,8 @@
 
 #include <utility>
 
+#include "agc_kernels.h"
+
 namespace agc {
 
 constexpr int kMaxWorkers = 256;
@@ -332,6 +334,7 @@ struct CsrView {
     const int* __restrict__ row_ptr;
     const int* __restrict__ col;
     const float* __restrict__ val;
+    const WindowRec* __restrict__ win;  // monotone-interval codes: one record per row + sentinel
 };
 
 template <bool RAGGED>
@@ -438,56 +441,105 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
 // supplies the up to W-1 older rows a worker may need), so all positions stay compile-time.
 template <int W>
 struct BatchShape {
-    static constexpr int BT = W >= 4 ? W : 4;  // rows per batch, >= W - 1
-    static constexpr int R = 2 * BT;
+    static constexpr int BT = 4;                                   // rows per batch
+    static constexpr int R = ((2 * BT + W - 1 + BT - 1) / BT) * BT;  // current + next batch + W-1 older rows
+    static constexpr int NB = R / BT;
 };
 
-template <int W, int HALF, class Epi>
-__device__ __forceinline__ void window_batch(float4 (&ring)[BatchShape<W>::R], const float* __restrict__ G,
-                                             int64_t ldg, int n, int k, const CsrView& B,
-                                             const LaneCoords& lc, int row0, int& i, Epi& epi)
+template <int W, int H>
+__device__ __forceinline__ void window_request(float4 (&ring)[BatchShape<W>::R], const float* __restrict__ G,
+                                               int64_t ldg, int k, const LaneCoords& lc, int row0)
 {
     constexpr int BT = BatchShape<W>::BT;
-    constexpr int R = BatchShape<W>::R;
     if (row0 < k) {  // one straight run of loads; a batch that straddles the end repeats row k-1
 #pragma unroll
         for (int r = 0; r < BT; ++r) {
             const int row = row0 + r < k ? row0 + r : k - 1;
-            ring[HALF * BT + r] = load_row4<false, true>(G + (int64_t)row * ldg, lc);
+            ring[H * BT + r] = load_row4<false, true>(G + (int64_t)row * ldg, lc);
         }
     }
+}
+
+// the part of a row's record the driver keeps in scalar registers
+struct WindowCur {
+    int lo, len;
+    float val[8];
+};
+
+__device__ __forceinline__ WindowCur load_window_rec(const WindowRec* rec)
+{
+    struct Head { int lo, len; };
+    struct Vals { float v[8]; };
+    const Head h = load_uniform(reinterpret_cast<const Head*>(rec));
+    const Vals v = load_uniform(reinterpret_cast<const Vals*>(rec->val));
+    WindowCur c;
+    c.lo = h.lo;
+    c.len = h.len;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c.val[u] = v.v[u];
+    return c;
+}
+
+template <int W, int H, class Epi>
+__device__ __forceinline__ void window_batch(float4 (&ring)[BatchShape<W>::R], const float* __restrict__ G,
+                                             int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
+                                             int row0, int& i, WindowCur& cur, Epi& epi)
+{
+    constexpr int BT = BatchShape<W>::BT;
+    constexpr int R = BatchShape<W>::R;
+    constexpr int NB = BatchShape<W>::NB;
+    // the batch requested one round ago has to be here now.  The empty asm makes its registers
+    // plain values for the compiler from here on: without it every later row step waits for all
+    // outstanding operations, the stores of the step before included.
+#pragma unroll
+    for (int r = 0; r < BT; ++r) {
+        float4& x = ring[H * BT + r];
+        asm volatile("" : "+v"(x.x), "+v"(x.y), "+v"(x.z), "+v"(x.w));
+    }
+    window_request<W, (H + 1) % NB>(ring, G, ldg, k, lc, row0 + BT);
 #pragma unroll
     for (int r = 0; r < BT; ++r) {
         const int lo = row0 + r - (W - 1);
-        while (i < n) {
-            const int e0 = load_uniform(B.row_ptr + i);
-            if (load_uniform(B.col + e0) != lo) break;
-            const int len = load_uniform(B.row_ptr + i + 1) - e0;
-            float4 f = mul4(load_uniform(B.val + e0), ring[(HALF * BT + r + R - (W - 1)) % R]);
+        while (cur.lo == lo) {  // the sentinel record ends the last run
+            const WindowCur nxt = load_window_rec(B.win + i + 1);  // in flight during this worker
+            float4 f = mul4(cur.val[0], ring[(H * BT + r + R - (W - 1)) % R]);
 #pragma unroll
             for (int u = 1; u < W; ++u)
-                if (u < len) f = fma4(load_uniform(B.val + e0 + u), ring[(HALF * BT + r + R - (W - 1) + u) % R], f);
+                if (u < cur.len) f = fma4(cur.val[u], ring[(H * BT + r + R - (W - 1) + u) % R], f);
             epi.worker_any(i, f);
+            cur = nxt;
             ++i;
         }
     }
 }
 
+template <int W, int H, class Epi>
+__device__ __forceinline__ void window_batches(float4 (&ring)[BatchShape<W>::R], const float* __restrict__ G,
+                                               int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
+                                               int row0, int steps, int& i, WindowCur& cur, Epi& epi)
+{
+    if constexpr (H < BatchShape<W>::NB) {
+        if (row0 < steps) {
+            window_batch<W, H>(ring, G, ldg, k, B, lc, row0, i, cur, epi);
+            window_batches<W, H + 1>(ring, G, ldg, k, B, lc, row0 + BatchShape<W>::BT, steps, i, cur, epi);
+        }
+    }
+}
+
 template <int W, class Epi>
-__device__ __forceinline__ void encode_window_batched(const float* __restrict__ G, int64_t ldg, int n, int k,
+__device__ __forceinline__ void encode_window_batched(const float* __restrict__ G, int64_t ldg, int k,
                                                       const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
-    constexpr int BT = BatchShape<W>::BT;
     constexpr int R = BatchShape<W>::R;
     float4 ring[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     int i = 0;
+    WindowCur cur = load_window_rec(B.win);
     const int steps = k + W - 1;  // the last worker may be anchored at row k-1
-    for (int row0 = 0; row0 < steps; row0 += R) {
-        window_batch<W, 0>(ring, G, ldg, n, k, B, lc, row0, i, epi);
-        if (row0 + BT < steps) window_batch<W, 1>(ring, G, ldg, n, k, B, lc, row0 + BT, i, epi);
-    }
+    window_request<W, 0>(ring, G, ldg, k, lc, 0);
+    for (int row0 = 0; row0 < steps; row0 += R)
+        window_batches<W, 0>(ring, G, ldg, k, B, lc, row0, steps, i, cur, epi);
 }
 
 // One block of 256 coordinates for all workers.  S > 0: cyclic band of width S; S < 0: monotone
@@ -503,7 +555,7 @@ __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_
         else encode_gather<true>(G, ldg, n, B, lc, epi);
     } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
         if (lc.wave_ragged) encode_gather<true>(G, ldg, n, B, lc, epi);
-        else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, n, k, B, lc, epi);
+        else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, k, B, lc, epi);
         else encode_window<-S>(G, ldg, n, k, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);

@@ -10,11 +10,23 @@ namespace agc {
 
 constexpr int kArgWorkers = 256;
 
+// Row i of a monotone-interval code as one 64-byte record, so that a kernel reads a worker's
+// structure with scalar loads whose address depends on i alone (no row_ptr -> col -> val chain).
+// Record n is a sentinel whose lo matches no row.
+struct WindowRec {
+    int lo;               // first column of the run
+    int len;              // 1..8 stored entries
+    int pad[6];
+    float val[8];         // the entries in stored order; unused ones are 0 and never read
+};
+static_assert(sizeof(WindowRec) == 64, "one record is 64 bytes");
+
 struct CodeDev {          // the code matrix B on the device
     const int* row_ptr;   // [n+1]
     const int* col;       // [nnz]
     const float* val;     // [nnz]
-    int band;             // 0: generic CSR; s>0: cyclic band with s entries per row
+    int band;             // 0: generic CSR; s>0: cyclic band with s entries per row; -W: monotone intervals
+    const WindowRec* win; // [n+1], monotone-interval codes only (else null)
 };
 
 // what the quantize pass needs to know about worker i, read with one scalar 32-byte load

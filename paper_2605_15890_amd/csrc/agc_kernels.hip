@@ -98,10 +98,10 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
         const LaneCoords lc = lane_coords(base, lane, a.d);
         if (MODE == 0) {
             EpiSumSq epi{accd, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, nullptr}, lc, epi);
         } else {
             EpiMaxAbs epi{accu, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, nullptr}, lc, epi);
         }
     } else {  // a block past the end of the vector contributes nothing
         for (int i = lane; i < a.n; i += kWave) {

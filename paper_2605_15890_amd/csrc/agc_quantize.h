@@ -19,6 +19,7 @@ struct QuantArgs {
     float* scales;  // bucket-wise scales only: n x nb
     int64_t nb;
     float* ghat;    // fused step only
+    const WindowRec* win;  // monotone-interval codes only; filled in by the launcher
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
     EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
                                groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
                                lc.wave_ragged, 0u, 0u, a.scales, a.nb, {0.f, 0.f, 0.f, 0.f}};
-    encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val}, lc, epi);
+    encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
         if (lc.nvalid == 4) {
@@ -275,8 +276,11 @@ __global__ __launch_bounds__(kWgThreads) void k_quantize(const float* __restrict
 
 template <int S, int BUCKET>
 static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const Workspace& ws,
-                                    const QuantArgs& a, hipStream_t stream)
+                                    const QuantArgs& args, hipStream_t stream)
 {
+    QuantArgs a = args;
+    a.win = code.win;
+    if (S < 0 && !a.win) return hipErrorInvalidValue;  // the window driver reads the records
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
     if (a.ghat)
