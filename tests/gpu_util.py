@@ -78,3 +78,22 @@ def cyclic_csr(rng, n, s):
     col = np.array([(i + u) % n for i in range(n) for u in range(s)], dtype=np.int32)
     val = rng.uniform(0.1, 1.0, n * s).astype(np.float32) * rng.choice([-1.0, 1.0], n * s).astype(np.float32)
     return row_ptr, col, val
+
+
+def monotone_csr(rng, n, k, max_len):
+    """Random code of the monotone-interval shape: runs of consecutive columns whose two ends
+    never decrease; several workers may start at the same column, columns may be skipped."""
+    row_ptr, col, val = [0], [], []
+    lo = hi = 0
+    for i in range(n):
+        lo = min(k - 1, max(lo, hi - int(rng.integers(0, 2))) + (int(rng.integers(0, 2)) if i else 0))
+        length = int(rng.integers(1, max_len + 1))
+        new_hi = min(k - 1, max(hi, lo + length - 1))
+        if new_hi - lo + 1 > max_len:
+            lo = new_hi - max_len + 1
+        hi = new_hi
+        cols = list(range(lo, hi + 1))
+        col += cols
+        val += list(rng.uniform(-1.0, 1.0, len(cols)).astype(np.float32))
+        row_ptr.append(len(col))
+    return np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(val, np.float32)

@@ -9,7 +9,7 @@ from oracle import agc_oracle as O
 from paper_2605_15890_amd import api
 from paper_2605_15890_amd import inputs as I
 
-from gpu_util import compare_with_oracle, cyclic_csr, random_csr, run_hip, to_device
+from gpu_util import compare_with_oracle, cyclic_csr, monotone_csr, random_csr, run_hip, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -325,30 +325,11 @@ def test_fused_step_equals_two_pass_step(bucket):
                 assert torch.equal(g0.view(torch.int32), g1.view(torch.int32))
 
 
-def _monotone_code(rng, n, k, max_len):
-    """Random code of the monotone-interval shape: runs of consecutive columns whose two ends
-    never decrease; several workers may start at the same column, columns may be skipped."""
-    row_ptr, col, val = [0], [], []
-    lo = hi = 0
-    for i in range(n):
-        lo = min(k - 1, max(lo, hi - int(rng.integers(0, 2))) + (int(rng.integers(0, 2)) if i else 0))
-        length = int(rng.integers(1, max_len + 1))
-        new_hi = min(k - 1, max(hi, lo + length - 1))
-        if new_hi - lo + 1 > max_len:
-            lo = new_hi - max_len + 1
-        hi = new_hi
-        cols = list(range(lo, hi + 1))
-        col += cols
-        val += list(rng.uniform(-1.0, 1.0, len(cols)).astype(np.float32))
-        row_ptr.append(len(col))
-    return np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(val, np.float32)
-
-
 @pytest.mark.parametrize("n,k,max_len,d", [(3, 1, 1, 300), (5, 9, 2, 1000), (9, 5, 2, 4097), (33, 20, 4, 2048),
                                            (40, 64, 4, 70001), (64, 64, 8, 5000), (200, 17, 8, 1025), (17, 200, 8, 3000)])
 def test_monotone_interval_codes_take_the_window_path(n, k, max_len, d):
     rng = np.random.default_rng(n * 1000 + k)
-    row_ptr, col, val = _monotone_code(rng, n, k, max_len)
+    row_ptr, col, val = monotone_csr(rng, n, k, max_len)
     longest = int(np.diff(row_ptr).max())
     want_path = 100 + (2 if longest <= 2 else 4 if longest <= 4 else 8)
     bits = rng.integers(1, 17, n).astype(np.uint8)

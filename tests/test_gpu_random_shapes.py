@@ -1,5 +1,5 @@
 """Randomised sweep of valid problem shapes on the GPU against the oracle: worker / partition
-counts, band widths and general sparse codes, ragged lengths, bit-widths 1..16, arrival masks,
+counts, band widths, monotone-interval and general sparse codes, ragged lengths, bit-widths 1..16, arrival masks,
 both scale kinds, per-vector and bucket-wise scales, fused and two-pass steps.  Every case is
 seeded; codes must be bit-exact, scales and estimates identical."""
 import numpy as np
@@ -8,19 +8,26 @@ import pytest
 from oracle import agc_oracle as O
 from paper_2605_15890_amd import api
 
-from gpu_util import cyclic_csr, random_csr, to_device
+from gpu_util import cyclic_csr, monotone_csr, random_csr, to_device
 
 pytestmark = pytest.mark.gpu
 
 
 def _case(seed):
     rng = np.random.default_rng(seed)
-    cyclic = rng.random() < 0.6
-    if cyclic:
+    kind = rng.random()
+    if kind < 0.45:      # cyclic band
         n = k = int(rng.integers(1, 40))
         s = int(rng.integers(1, min(8, k) + 1))
         code = cyclic_csr(rng, n, s)
         path = s
+    elif kind < 0.75:    # monotone intervals (window drivers)
+        n, k = int(rng.integers(1, 70)), int(rng.integers(1, 70))
+        code = monotone_csr(rng, n, k, int(rng.choice([1, 2, 3, 4, 6, 8])))
+        longest = int(np.diff(code[0]).max())
+        path = 100 + (2 if longest <= 2 else 4 if longest <= 4 else 8)
+        if n == k and np.array_equal(code[1], np.arange(n)) and longest == 1:
+            path = 1     # a diagonal code is also a cyclic band of width 1, which is looked for first
     else:
         n, k = int(rng.integers(1, 40)), int(rng.integers(1, 40))
         code = random_csr(rng, n, k, int(rng.integers(1, 6)))
@@ -39,7 +46,7 @@ def _case(seed):
                 seed=int(rng.integers(0, 2 ** 62)), step=int(rng.integers(0, 2 ** 40)))
 
 
-@pytest.mark.parametrize("seed", range(48))
+@pytest.mark.parametrize("seed", range(72))
 def test_random_case(seed):
     import torch
     c = _case(1000 + seed)
