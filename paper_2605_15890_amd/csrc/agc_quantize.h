@@ -189,17 +189,19 @@ struct EpiQuant {
             if (q.arrived) {  // wave-uniform
                 const float coef = BUCKET == 0 ? q.coef : q.coef * scale;
                 const float fv[4] = {f.x, f.y, f.z, f.w};
-                if (b >= 2) {  // +-level: the level as a float with the sign bit of f
+                // the decoded value: +-level (the level as a float with the sign bit of f), or +-1
+                // for a one-bit worker; one fused multiply-add per coordinate either way
+                float v[4];
+                if (b >= 2) {
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const float v = __uint_as_float(__float_as_uint((float)lev[t]) |
-                                                        (__float_as_uint(fv[t]) & 0x80000000u));
-                        acc[t] = fmaf(coef, v, acc[t]);
-                    }
-                } else {  // one-bit worker: +-1
+                    for (int t = 0; t < 4; ++t)
+                        v[t] = __uint_as_float(__float_as_uint((float)lev[t]) | (__float_as_uint(fv[t]) & 0x80000000u));
+                } else {
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) acc[t] = fmaf(coef, lev[t] ? 1.0f : -1.0f, acc[t]);
+                    for (int t = 0; t < 4; ++t) v[t] = lev[t] ? 1.0f : -1.0f;
                 }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc[t] = fmaf(coef, v[t], acc[t]);
             }
         }
 
