@@ -96,6 +96,39 @@ def test_general_codes(n, k):
                         tag="interval code")
 
 
+@pytest.mark.parametrize("kind", ["cyclic8", "cyclic3", "window", "general_wide"])
+def test_maximum_worker_count(kind):
+    """n = 256 workers, the most the library takes (their arguments fill the kernel argument
+    block), with every driver: cyclic bands, monotone intervals, and a general code over k = 4096
+    partitions.  Bit-widths cover 1..16, both scale kinds, ragged d."""
+    rng = np.random.default_rng({"cyclic8": 1, "cyclic3": 2, "window": 3, "general_wide": 4}[kind])
+    n = api.AGC_MAX_WORKERS
+    if kind.startswith("cyclic"):
+        k, s = n, int(kind[-1])
+        row_ptr, col, val = cyclic_csr(rng, n, s)
+        path = s
+    elif kind == "window":
+        k = 300
+        row_ptr, col, val = monotone_csr(rng, n, k, 8)
+        path = 108
+    else:
+        k = 4096
+        row_ptr, col, val = random_csr(rng, n, k, 5)
+        path = 0
+    d = 777
+    bits = ((np.arange(n) % 16) + 1).astype(np.uint8)
+    rng.shuffle(bits)
+    w = rng.uniform(0.5, 2, n).astype(np.float32)
+    mask = (rng.random(n) < 0.8).astype(np.uint8)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    Gd = to_device(G)
+    for scale_mode in MODES:
+        out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 11, 12, scale_mode, allow_1bit=True,
+                      expect_path=path)
+        compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 11, 12, scale_mode, out,
+                            tag=f"n=256 {kind} mode={scale_mode}")
+
+
 def test_degenerate_inputs():
     """All stragglers (estimate exactly 0), everyone arrived, an all-zero coded vector
     (scale 0), and max-abs coordinates that sit exactly on the top level."""
