@@ -178,3 +178,69 @@ def test_full_size_bucket_scales_sampled_parity(name, scale_mode, nwin):
         first_pad_byte = (d * b + 7) // 8
         assert not streams[i][first_pad_byte:].any()
     ctx.close()
+
+
+@pytest.mark.parametrize("bucket", [0, 256])
+def test_coordinates_beyond_2_pow_31(bucket):
+    """One worker, one partition, d = 2^31 + 3077 coordinates (8.6 GB of gradient) at 16 bits, so
+    that coordinate indices pass 2^31 and the packed stream passes byte 2^32.  Scales (the
+    whole-vector one, or with bucket-wise scales those of the sampled windows), codes and
+    estimate in windows at the start, across coordinate 2^31 (= byte 2^32 of the stream) and at
+    the ragged end; the fused step and the stand-alone decode must agree everywhere."""
+    import torch
+    d = (1 << 31) + 3077
+    n = k = 1
+    b = 16
+    bits = np.array([b], np.uint8)
+    w = np.array([1.7], np.float32)
+    mask = np.array([1], np.uint8)
+    row_ptr, col, val = np.array([0, 1], np.int32), np.array([0], np.int32), np.array([0.75], np.float32)
+    seed, step = 0x1234567890ABCDEF, (1 << 33) + 5
+    scale_mode = api.AGC_SCALE_L2 if bucket else api.AGC_SCALE_MAXABS
+    G = api.padded_rows(k, d)
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    G.normal_(generator=gen)
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, bucket=bucket)
+    try:
+        ctx.agc_set_code(row_ptr, col, val)
+        assert ctx.agc_code_path() == 1
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        scales.fill_(float("nan"))
+        ctx.agc_step(G, bits, w, mask, seed, step, codes, scales, ghat)
+        torch.cuda.synchronize()
+        print(f"[2^31 bucket={bucket}] step done", flush=True)
+        assert not torch.isnan(scales).any()
+        ghat2 = torch.empty_like(ghat)
+        ctx.agc_decode(codes, scales, bits, w, mask, ghat2)
+        torch.cuda.synchronize()
+        assert torch.equal(ghat.view(torch.int32), ghat2.view(torch.int32))
+        del ghat2
+        G_host = G.cpu().numpy()[:, :d]
+        stream = codes[0].cpu().numpy()
+        scales_h = scales.cpu().numpy()
+        ghat_h = ghat.cpu().numpy()
+    finally:
+        ctx.close()
+    del G, codes, ghat
+    torch.cuda.empty_cache()
+    print(f"[2^31 bucket={bucket}] oracle", flush=True)
+    csr = O.Csr(row_ptr, col, val, k)
+    assert stream.size == O.code_bytes(d, b) and stream.size > (1 << 32)
+    if not bucket:
+        want_scale = np.float32(np.abs(G_host[0]).max()) * np.float32(0.75)   # |0.75 g| is monotone in |g|
+        assert scales_h[0] == want_scale
+    for m0 in [0, (1 << 31) - 2048, d - WINDOW - (d - WINDOW) % 256]:
+        m1 = min(d, m0 + WINDOW)
+        got = O.unpack_range(stream, b, m0, m1)
+        if bucket:
+            want, want_sc = O.codes_bucket_range(G_host, csr, 0, b, scale_mode, seed, step, m0, m1)
+            got_sc = scales_h[0, m0 // 256: m0 // 256 + want_sc.size]
+            assert np.array_equal(want_sc.view(np.uint32), got_sc.view(np.uint32)), m0
+            o_gh = O.decode_bucket([stream], scales_h, bits, w, mask, d, m0, m1)
+        else:
+            want = O.codes_range(G_host, csr, 0, b, want_scale, seed, step, m0, m1)
+            o_gh = O.decode([stream], scales_h, bits, w, mask, d, m0, m1)
+        assert np.array_equal(want, got), m0
+        assert np.array_equal(o_gh.view(np.uint32), ghat_h[m0:m1].view(np.uint32)), m0
+    first_pad_byte = (d * b + 7) // 8
+    assert not stream[first_pad_byte:].any()
