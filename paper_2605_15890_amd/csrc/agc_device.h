@@ -85,7 +85,13 @@ __device__ __forceinline__ uint32_t wave_max_nonneg_bits(float x)
     v = max(v, dpp_u32<kDppRowMirror>(v));  // every 16-lane row now holds its maximum
     const uint32_t r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
     const uint32_t r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
-    return max(max(r0, r1), max(r2, r3));
+    // the four row maxima are wave-uniform: combine them on the scalar unit (left to itself the
+    // compiler moves them back into vector registers for a three-operand maximum)
+    uint32_t a, b, m;
+    asm("s_max_u32 %0, %1, %2" : "=s"(a) : "s"(r0), "s"(r1) : "scc");
+    asm("s_max_u32 %0, %1, %2" : "=s"(b) : "s"(r2), "s"(r3) : "scc");
+    asm("s_max_u32 %0, %1, %2" : "=s"(m) : "s"(a), "s"(b) : "scc");
+    return m;
 }
 
 template <int CTRL>

@@ -31,7 +31,8 @@ struct CodeDev {          // the code matrix B on the device
 
 // what the quantize pass needs to know about worker i, read with one scalar 32-byte load
 struct WorkerQ {
-    float inv16;          // L_i * 2^16 / scale_i (2^15 / scale_i for a one-bit worker)
+    float inv16;          // L_i * 2^16 / scale_i (2^15 / scale_i for a one-bit worker); with bucket-wise
+                          // scales the numerator alone, the division happens per block
     uint32_t bits;
     void* codes;          // packed stream of the worker
     // fused quantize+decode pass only: the decode weight of worker i (w_i * scale_i / L_i; with

@@ -307,7 +307,10 @@ __global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams 
     const int i = threadIdx.x;
     if (i >= n) return;
     const int b = out.bits[i];
-    WorkerQ e{0.0f, (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
+    // bucket-wise scales: the multiplier is num / scale with the block's own scale; the record
+    // carries the numerator L * 2^16 (2^15 for a one-bit worker)
+    const float num = b >= 2 ? (float)(((1u << (b - 1)) - 1u) << 16) : 32768.0f;
+    WorkerQ e{num, (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
     if (sw.fuse) {
         const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
         e.coef = (float)((double)sw.w[i] / L);
