@@ -442,9 +442,11 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
 // The same driver for epilogues that store inside the worker loop (the quantize pass).  Stores
 // and loads share one outstanding-operation counter on this hardware, so behind a loop of unknown
 // length the compiler can only wait for everything; a rolling prefetch would be drained at every
-// row.  Here the rows arrive in batches of BT: one batch is requested, waited for as a whole, and
-// then its BT row steps run without further loads.  The ring holds two batches (the previous one
-// supplies the up to W-1 older rows a worker may need), so all positions stay compile-time.
+// row.  Here the rows arrive in batches of BT: while the BT row steps of one batch run, the next
+// batch is in flight; it is waited for as a whole when its turn comes.  The ring holds the
+// current batch, the next one and the up to W-1 older rows a worker may still need, rounded up to
+// whole batches so that all positions stay compile-time.  The structure of worker i comes from
+// its 64-byte record, read one worker ahead.
 template <int W>
 struct BatchShape {
     static constexpr int BT = 4;                                   // rows per batch
