@@ -377,10 +377,30 @@ __device__ __forceinline__ void encode_gather(const float* __restrict__ G, int64
 // multiplied by zero: the sum must have exactly the stored terms).  Several workers, or none, may
 // be anchored at the same row.
 // ---------------------------------------------------------------------------------------
+// the part of a row's record the driver keeps in scalar registers
+struct WindowCur {
+    int lo, len;
+    float val[8];
+};
+
+__device__ __forceinline__ WindowCur load_window_rec(const WindowRec* rec)
+{
+    struct Head { int lo, len; };
+    struct Vals { float v[8]; };
+    const Head h = load_uniform(reinterpret_cast<const Head*>(rec));
+    const Vals v = load_uniform(reinterpret_cast<const Vals*>(rec->val));
+    WindowCur c;
+    c.lo = h.lo;
+    c.len = h.len;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c.val[u] = v.v[u];
+    return c;
+}
+
 template <int W, int r, bool STEADY, class Epi>
 __device__ __forceinline__ void window_step(float4 (&ring)[RingShape<W>::R], const float*& next_row,
-                                            int64_t ldg, int n, int k, const CsrView& B,
-                                            const LaneCoords& lc, int j0, int& i, Epi& epi)
+                                            int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
+                                            int j0, int& i, WindowCur& cur, Epi& epi)
 {
     constexpr int P = RingShape<W>::P;
     constexpr int R = RingShape<W>::R;
@@ -390,30 +410,29 @@ __device__ __forceinline__ void window_step(float4 (&ring)[RingShape<W>::R], con
         next_row += (j + P + 1 < k) ? ldg : 0;
     }
     const int lo = j - (W - 1);
-    while (i < n) {
-        const int e0 = B.row_ptr[i];
-        if (B.col[e0] != lo) break;
-        const int len = B.row_ptr[i + 1] - e0;
-        float4 f = mul4(B.val[e0], ring[(r + R - (W - 1)) % R]);
+    while (cur.lo == lo) {  // the sentinel record ends the last run
+        const WindowCur nxt = load_window_rec(B.win + i + 1);
+        float4 f = mul4(cur.val[0], ring[(r + R - (W - 1)) % R]);
 #pragma unroll
         for (int u = 1; u < W; ++u)
-            if (u < len) f = fma4(B.val[e0 + u], ring[(r + R - (W - 1) + u) % R], f);
+            if (u < cur.len) f = fma4(cur.val[u], ring[(r + R - (W - 1) + u) % R], f);
         epi.worker_any(i, f);
+        cur = nxt;
         ++i;
     }
 }
 
 template <int W, bool STEADY, class Epi, int... Rs>
 __device__ __forceinline__ void window_round(float4 (&ring)[RingShape<W>::R], const float*& next_row,
-                                             int64_t ldg, int n, int k, const CsrView& B,
-                                             const LaneCoords& lc, int j0, int& i, Epi& epi,
+                                             int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
+                                             int j0, int& i, WindowCur& cur, Epi& epi,
                                              std::integer_sequence<int, Rs...>)
 {
-    (window_step<W, Rs, STEADY>(ring, next_row, ldg, n, k, B, lc, j0, i, epi), ...);
+    (window_step<W, Rs, STEADY>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi), ...);
 }
 
 template <int W, class Epi>
-__device__ __forceinline__ void encode_window(const float* __restrict__ G, int64_t ldg, int n, int k,
+__device__ __forceinline__ void encode_window(const float* __restrict__ G, int64_t ldg, int k,
                                               const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     constexpr int P = RingShape<W>::P;
@@ -431,12 +450,13 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
         }
     }
     int i = 0;
+    WindowCur cur = load_window_rec(B.win);
     int j0 = 0;
     const int steps = k + W - 1;  // the last worker may be anchored at row k-1
     for (; j0 + R - 1 + P < k; j0 += R)  // every prefetch of the round exists
-        window_round<W, true>(ring, next_row, ldg, n, k, B, lc, j0, i, epi, seq);
+        window_round<W, true>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
     for (; j0 < steps; j0 += R)
-        window_round<W, false>(ring, next_row, ldg, n, k, B, lc, j0, i, epi, seq);
+        window_round<W, false>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
 }
 
 // The same driver for epilogues that store inside the worker loop (the quantize pass).  Stores
@@ -466,26 +486,6 @@ __device__ __forceinline__ void window_request(float4 (&ring)[BatchShape<W>::R],
             ring[H * BT + r] = load_row4<false, true>(G + (int64_t)row * ldg, lc);
         }
     }
-}
-
-// the part of a row's record the driver keeps in scalar registers
-struct WindowCur {
-    int lo, len;
-    float val[8];
-};
-
-__device__ __forceinline__ WindowCur load_window_rec(const WindowRec* rec)
-{
-    struct Head { int lo, len; };
-    struct Vals { float v[8]; };
-    const Head h = load_uniform(reinterpret_cast<const Head*>(rec));
-    const Vals v = load_uniform(reinterpret_cast<const Vals*>(rec->val));
-    WindowCur c;
-    c.lo = h.lo;
-    c.len = h.len;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) c.val[u] = v.v[u];
-    return c;
 }
 
 template <int W, int H, class Epi>
@@ -564,7 +564,7 @@ __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_
     } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
         if (lc.wave_ragged) encode_gather<true>(G, ldg, n, B, lc, epi);
         else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, k, B, lc, epi);
-        else encode_window<-S>(G, ldg, n, k, B, lc, epi);
+        else encode_window<-S>(G, ldg, k, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);

@@ -33,6 +33,7 @@ struct ScaleArgs {
     int64_t nseg;
     uint32_t* part_max;
     double* part_sq;
+    const WindowRec* win;  // monotone-interval codes only
 };
 
 // the same 32-bit word seen as device memory (store without address-space checks)
@@ -98,10 +99,10 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
         const LaneCoords lc = lane_coords(base, lane, a.d);
         if (MODE == 0) {
             EpiSumSq epi{accd, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, nullptr}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
         } else {
             EpiMaxAbs epi{accu, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, nullptr}, lc, epi);
+            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
         }
     } else {  // a block past the end of the vector contributes nothing
         for (int i = lane; i < a.n; i += kWave) {
@@ -178,7 +179,8 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream)
 {
-    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq};
+    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq, code.win};
+    if (code.band < 0 && !code.win) return hipErrorInvalidValue;  // the window driver reads the records
     switch (code.band) {
         case 1: return launch_scale_pass_s<1>(G, code, a, scale_mode, stream);
         case 2: return launch_scale_pass_s<2>(G, code, a, scale_mode, stream);
