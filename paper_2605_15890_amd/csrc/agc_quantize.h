@@ -246,8 +246,9 @@ struct EpiQuant {
 template <int S, int BUCKET, bool FUSE>
 // The compiler is told to plan for four waves per SIMD: with a register count just under the
 // five-wave limit it otherwise schedules for five and gives up instruction-level parallelism;
-// measured 1.45 ms against 1.51 ms on the metric workload (three: 1.51 ms).
-__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_quantize(const float* __restrict__ G,
+// measured 1.45 ms against 1.51 ms on the metric workload (three: 1.51 ms).  The gather driver
+// (S == 0) lives on occupancy instead and keeps the default.
+__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(S == 0 ? 1 : 4, S == 0 ? 8 : 4))) void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,

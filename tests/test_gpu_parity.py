@@ -77,8 +77,8 @@ def test_every_band_width(s):
 
 @pytest.mark.parametrize("n,k", [(1, 1), (1, 7), (7, 1), (5, 9), (9, 5), (33, 20), (64, 64), (200, 17)])
 def test_general_codes(n, k):
-    """Arbitrary sparse codes (empty rows, n != k, repeated use of one partition) take the
-    generic path; the optimally structured interval code of Sec. III-A as well."""
+    """Arbitrary sparse codes (empty rows, long rows, n != k, repeated use of one partition) take
+    the gather path; the optimally structured interval code of Sec. III-A follows."""
     rng = np.random.default_rng(n * 1000 + k)
     d = int(rng.integers(1500, 6000))
     G = rng.standard_normal((k, d)).astype(np.float32)
@@ -86,9 +86,18 @@ def test_general_codes(n, k):
     bits = rng.integers(2, 9, n).astype(np.uint8)
     w = rng.uniform(0.5, 2, n).astype(np.float32)
     mask = (rng.random(n) < 0.6).astype(np.uint8)
-    row_ptr, col, val = random_csr(rng, n, k)
-    out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2)
-    compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2, out, tag="random csr")
+    for max_nnz in (4, 8, 13):
+        row_ptr, col, val = random_csr(rng, n, k, max_nnz)
+        outs = []
+        for force_generic in (False, True):
+            out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2,
+                          force_generic=force_generic,
+                          # a tiny random code may happen to be a band or a run of intervals
+                          expect_path=0 if force_generic or n >= 30 else None)
+            compare_with_oracle(G, k, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_L2, out,
+                                tag=f"random csr max_nnz={max_nnz} generic={force_generic}")
+            outs.append(out)
+        assert all(np.array_equal(a, b) for a, b in zip(outs[0][0], outs[1][0]))
     p = rng.uniform(0.05, 0.6, n)
     row_ptr, col, val, w2 = api.agc_build_code(n, k, p, bits, 0.3)
     out = run_hip(Gd, n, k, d, row_ptr, col, val, bits, w2, mask, 78, 4, api.AGC_SCALE_MAXABS)
