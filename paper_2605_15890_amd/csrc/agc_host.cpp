@@ -252,7 +252,14 @@ agc_status agc_build_code(int n, int k, const double* p, const uint8_t* bits, do
     row_ptr[0] = 0;
     for (int i = 0; i < n; ++i) {
         const double Y = cinv[i] * (double)k / tot;
-        const double R = (i == n - 1) ? (double)k : R_prev + Y;
+        double R = (i == n - 1) ? (double)k : R_prev + Y;
+        // A segment end that should fall on a partition boundary lands a few units in the last
+        // place beside it after the running sum; left there it would add an entry of ~1e-16 (one
+        // more partition for the worker to compute, one more row in its window).  Ends within
+        // 1e-12 * k of an integer are moved onto it; the segments still tile [0, k], so every
+        // column still sums to 1.
+        const double R_int = std::nearbyint(R);
+        if (std::fabs(R - R_int) <= 1e-12 * (double)k) R = R_int;
         // overlap of [R_prev, R] with the unit segment [j-1, j] of partition j (1-based)
         int j_first = (int)std::floor(R_prev) + 1;
         int j_last = std::min(k, (int)std::ceil(R));

@@ -111,10 +111,33 @@ def test_interval_code_matches_oracle(n, k):
     row_ptr, col, val, w = api.agc_build_code(n, k, p, bits, pc)
     alpha = D.interval_code(D.row_targets(D.c_weights(p, bits, pc), k), k)
     dense = O.Csr(row_ptr, col, val, k).dense()
-    keep = alpha > 1e-9          # entries at rounding level may or may not be stored
+    keep = alpha > 1e-9          # the library moves segment ends at rounding distance onto the boundary
     assert np.allclose(dense, alpha, atol=1e-6)
     assert np.all(dense[keep] > 0)
-    assert len(col) <= n + k - 1 + 2
+    assert len(col) <= n + k - 1                                  # Sec. III-A: at most n + k - 1 entries
+    assert np.all(val > 1e-11 * k)                                # no entry at rounding level
+    assert np.allclose(dense.astype(np.float64).sum(axis=0), 1.0, atol=2e-7)
+
+
+@pytest.mark.parametrize("n,k", [(4, 4), (6, 12), (12, 6), (64, 64), (256, 256)])
+def test_interval_code_of_equal_workers_has_no_slivers(n, k):
+    """Equal workers have equal segments whose ends fall on partition boundaries wherever
+    i*k/n is an integer; the running sum misses those by rounding, and the construction must
+    not turn the miss into stored entries: exactly as many entries as the exact-arithmetic
+    construction has (Sec. III-A), n = k giving the identity."""
+    from fractions import Fraction
+    p = np.full(n, 0.3)
+    bits = np.full(n, 3, np.uint8)
+    row_ptr, col, val, w = api.agc_build_code(n, k, p, bits, 0.7)
+    exact = 0
+    for i in range(n):
+        lo, hi = Fraction(i * k, n), Fraction((i + 1) * k, n)
+        exact += sum(1 for j in range(k) if min(hi, j + 1) - max(lo, j) > 0)
+    assert len(col) == exact
+    if n == k:
+        assert np.array_equal(col, np.arange(n)) and np.array_equal(val, np.ones(n, np.float32))
+    ctx_shape_ok = all(row_ptr[i + 1] - row_ptr[i] <= 8 for i in range(n))
+    assert ctx_shape_ok
     assert np.allclose(w, 1 / (1 - p), rtol=1e-6)
     for i in range(n):   # columns ascending inside a row
         c = col[row_ptr[i]:row_ptr[i + 1]]
