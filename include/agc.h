@@ -186,6 +186,25 @@ agc_status agc_decode2(agc_ctx *ctx, void *const *codes_dev, const float *scales
                        const uint8_t *bits_host, const float *w_host, const float *v_host,
                        const uint8_t *mask_host, float *ghat_dev, float *ghat2_dev, void *hip_stream);
 
+/*
+ * agc_decode for callers that cannot allocate device memory and therefore cannot hold a context:
+ * code under HIP graph capture, tight serving loops on the master, harnesses that forbid
+ * hipMalloc.  No context: n_workers, d and bucket (0, or 256 for bucket-wise scales) are passed
+ * directly; a one-bit stream is always accepted.  Same kernels, same arithmetic and the same bits
+ * in g_hat as agc_decode.  The small tables the decode kernel reads (one 16-byte record and one
+ * row pointer per arrived worker) live in a fixed 6144-byte device array inside the library,
+ * which every GPU the library runs on holds until the process ends; hence n_workers <= 256
+ * (AGC_ESHAPE with a message otherwise).  The call itself and everything below it performs no
+ * hipMalloc/hipFree; the first call on a device looks the array's address up once (make that
+ * call before starting a graph capture).  All calls on one GPU share the array: calls that
+ * overlap on one GPU (different streams without an event between them, or different threads)
+ * race on it and must be serialised by the caller.  Errors are reported through
+ * agc_last_error(NULL).
+ */
+agc_status agc_decode_noalloc(int n_workers, int64_t d, int bucket, void *const *codes_dev,
+                              const float *scales_dev, const uint8_t *bits_host, const float *w_host,
+                              const uint8_t *mask_host, float *ghat_dev, void *hip_stream);
+
 /* One whole pass, with the outputs of agc_encode_quantize followed by agc_decode on the same
  * stream (codes, scales, g_hat; identical bits).  By default the quantize kernel also forms
  * g_hat from the codes it has just produced, in the order and arithmetic of agc_decode, so the

@@ -21,7 +21,7 @@ KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
-    "agc_scales_per_worker", "agc_decode2", "agc_adam_update", "agc_second_moment_decoder",
+    "agc_scales_per_worker", "agc_decode2", "agc_decode_noalloc", "agc_adam_update", "agc_second_moment_decoder",
     "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_build_cyclic_code_opt", "agc_check_unbiased",
@@ -82,6 +82,8 @@ def load():
     L.agc_scales_per_worker.restype = C.c_int64
     L.agc_decode2.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _f32p, _u8p, _vp, _vp, _vp]
     L.agc_decode2.restype = C.c_int
+    L.agc_decode_noalloc.argtypes = [C.c_int, C.c_int64, C.c_int, C.POINTER(_vp), _vp, _u8p, _f32p, _u8p, _vp, _vp]
+    L.agc_decode_noalloc.restype = C.c_int
     L.agc_adam_update.argtypes = [_vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, C.c_float, C.c_float,
                                   C.c_int64, C.c_int64, _vp]
     L.agc_adam_update.restype = C.c_int
@@ -417,6 +419,28 @@ def agc_adam_update(beta, m1, m2, ghat, ghat2, lr, beta1, beta2, eps, t, stream=
                                 _stream_handle(stream))
     if st != AGC_OK:
         raise AgcError(st, "agc_adam_update")
+
+
+def agc_decode_noalloc(n, d, bucket, codes, scales, bits, w, mask, ghat, stream=None, check=True):
+    """Context-free decode for callers that cannot allocate: same outputs as Context.agc_decode."""
+    bits, w, mask = _np(bits, np.uint8), _np(w, np.float32), _np(mask, np.uint8)
+    L = load()
+    if len(codes) != n or len(bits) != n or len(w) != n or len(mask) != n:
+        raise AgcError(AGC_ESHAPE, f"expected {n} streams, bit-widths, weights and mask entries")
+    if n <= AGC_MAX_WORKERS:   # sizes the library would refuse are left for it to refuse
+        for i, t in enumerate(codes):
+            need = agc_code_bytes(d, int(bits[i]))
+            if need and t.numel() * t.element_size() < need:
+                raise AgcError(AGC_ESHAPE, f"codes[{i}] is smaller than d={d}, bits={int(bits[i])} require")
+        per = (int(d) + 255) // 256 if bucket == 256 else 1
+        if scales.numel() < n * per or ghat.numel() < d:
+            raise AgcError(AGC_ESHAPE, "scales or ghat tensor too small")
+    st = L.agc_decode_noalloc(int(n), int(d), int(bucket), Context._code_ptrs(codes),
+                              C.c_void_p(scales.data_ptr()), _ptr(bits, _u8p), _ptr(w, _f32p), _ptr(mask, _u8p),
+                              C.c_void_p(ghat.data_ptr()), _stream_handle(stream))
+    if check and st != AGC_OK:
+        raise AgcError(st, L.agc_last_error(None).decode())
+    return st
 
 
 def agc_calibration_copy(dst, src, nbytes, stream=None):

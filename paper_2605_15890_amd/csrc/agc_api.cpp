@@ -459,6 +459,38 @@ agc_status agc_decode2(agc_ctx* c, void* const* codes, const float* scales, cons
     return t.end();
 }
 
+agc_status agc_decode_noalloc(int n, int64_t d, int bucket, void* const* codes, const float* scales,
+                              const uint8_t* bits, const float* w, const uint8_t* mask, float* ghat,
+                              void* hip_stream)
+{
+    if (n < 1 || d < 1 || d > ((int64_t)1 << 33)) return fail(nullptr, AGC_ESHAPE, "n_workers and d must be positive, d <= 2^33");
+    if (n > AGC_MAX_WORKERS)
+        return fail(nullptr, AGC_ESHAPE, "agc_decode_noalloc: n_workers = " + std::to_string(n) +
+                                             " exceeds the " + std::to_string(AGC_MAX_WORKERS) +
+                                             " workers the fixed device scratch array holds");
+    if (bucket != 0 && bucket != 256) return fail(nullptr, AGC_EINVAL, "bucket must be 0 or 256");
+    if (!codes || !scales || !bits || !w || !mask || !ghat) return fail(nullptr, AGC_EINVAL, "null argument");
+    if (reinterpret_cast<uintptr_t>(ghat) & 15u) return fail(nullptr, AGC_EALIGN, "ghat_dev is not 16-byte aligned");
+    agc::DecodeStreams ds{};
+    int n_arrived = 0;
+    for (int i = 0; i < n; ++i) {
+        if (bits[i] < 1 || bits[i] > AGC_MAX_BITS)
+            return fail(nullptr, AGC_EBITS, "bit-width of worker " + std::to_string(i) + " is " +
+                                                std::to_string((int)bits[i]) + " (allowed: 1..16)");
+        if (!codes[i]) return fail(nullptr, AGC_EINVAL, "codes_dev[" + std::to_string(i) + "] is null");
+        if (reinterpret_cast<uintptr_t>(codes[i]) & 15u)
+            return fail(nullptr, AGC_EALIGN, "codes_dev[" + std::to_string(i) + "] is not 16-byte aligned");
+        ds.codes[i] = codes[i];
+        ds.w[i] = w[i];
+        ds.bits[i] = bits[i];
+        ds.slot[i] = mask[i] ? (uint16_t)n_arrived++ : (uint16_t)0xFFFF;
+    }
+    hipError_t e = agc::launch_decode_static(n, n_arrived, d, ds, scales, bucket ? (d + 255) / 256 : 0, ghat,
+                                             reinterpret_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return hip_fail(nullptr, e, "allocation-free decode");
+    return AGC_OK;
+}
+
 agc_status agc_adam_update(float* beta_dev, float* m1_dev, float* m2_dev, const float* ghat_dev,
                            const float* ghat2_dev, float lr, float beta1, float beta2, float eps,
                            int64_t t, int64_t d, void* hip_stream)

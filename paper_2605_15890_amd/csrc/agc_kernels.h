@@ -119,6 +119,12 @@ hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& i
 hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& in, const DecodeSecond& second,
                           const float* scales, int64_t nb, const Workspace& ws, float* ghat, float* ghat2,
                           hipStream_t stream);
+// The decode of launch_decode with its two small tables (arrived workers, their rows of
+// bucket-wise scales) in a fixed device array of kStaticScratchBytes bytes instead of a context's
+// workspace: no allocation anywhere, n <= 256.  Calls on one GPU share the array.
+constexpr size_t kStaticScratchBytes = 6144;
+hipError_t launch_decode_static(int n, int n_arrived, int64_t d, const DecodeStreams& in, const float* scales,
+                                int64_t nb, float* ghat, hipStream_t stream);
 // Adam update that takes its first moment from ghat and its second moment from ghat2.
 hipError_t launch_adam_update(float* beta, float* m1, float* m2, const float* ghat, const float* ghat2,
                               float lr, float beta1, float beta2, float eps, float corr1, float corr2,

@@ -14,6 +14,8 @@
 // path, hence no MFMA.  Per-worker parameters are read with scalar loads from small device
 // tables, never with vector loads, so that waiting for them does not drain the queue of
 // outstanding row loads.
+#include <mutex>
+
 #include "agc_device.h"
 #include "agc_kernels.h"
 #include "agc_quantize.h"
@@ -528,6 +530,65 @@ hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& 
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
     launch_decode_kernel<true>(nb > 0, grid, stream, ws, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Decode for callers that cannot allocate (HIP graph capture, tight serving loops): the table
+// of arrived workers and their rows of bucket-wise scales, which agc_decode keeps in the
+// context's workspace, live in a fixed device array instead.  Each GPU holds its own copy of
+// the array at its own address; host code only ever uses the address that
+// hipGetSymbolAddress returned for the device that was current.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kScratchTableBytes = sizeof(WorkerD) * kMaxWorkers;          // 4096
+constexpr size_t kScratchRowsBytes = sizeof(const float*) * kMaxWorkers;      // 2048
+constexpr size_t kScratchBytes = kScratchTableBytes + kScratchRowsBytes;
+static_assert(kScratchBytes == kStaticScratchBytes, "size stated in the launch interface");
+static_assert(kScratchTableBytes % 256 == 0, "the rows of scales start on an aligned offset");
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices];  // per device: the device address of `scratch`, null = not resolved yet
+}  // namespace
+
+hipError_t launch_decode_static(int n, int n_arrived, int64_t d, const DecodeStreams& in, const float* scales,
+                                int64_t nb, float* ghat, hipStream_t stream)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        if (!g_scratch_ptr[dev]) {  // first call on this device, which is the current one
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = p;
+        }
+        base = g_scratch_ptr[dev];
+    }
+    WorkerD* wd = reinterpret_cast<WorkerD*>(base);
+    const float** srow = reinterpret_cast<const float**>(static_cast<unsigned char*>(base) + kScratchTableBytes);
+    // the prologue rewrites every entry that the decode kernel reads (slots 0..n_arrived-1), so
+    // nothing of the previous call's contents has to be cleared
+    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, wd, srow);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    DecodeArgs a{n_arrived, d, ghat, nullptr};
+    const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
+    const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
+    if (nb > 0)
+        hipLaunchKernelGGL((k_decode<false, true>), dim3(grid), dim3(kWgThreads), 0, stream, wd, (const float*)nullptr,
+                           (const float* const*)srow, a);
+    else
+        hipLaunchKernelGGL((k_decode<false, false>), dim3(grid), dim3(kWgThreads), 0, stream, wd,
+                           (const float*)nullptr, (const float* const*)nullptr, a);
     return hipGetLastError();
 }
 

@@ -49,6 +49,24 @@ def test_create_rejects_bad_shapes_without_touching_the_gpu():
     assert lib.agc_create(ctypes.byref(h), 4, 4, 16, ctypes.byref(bad)) == api.AGC_EINVAL
 
 
+def test_noalloc_decode_rejects_sizes_beyond_its_fixed_scratch_without_touching_the_gpu():
+    lib = api.load()
+    n = api.AGC_MAX_WORKERS + 1
+    ptrs = (ctypes.c_void_p * n)()
+    bits = np.full(n, 4, np.uint8)
+    w = np.ones(n, np.float32)
+    mask = np.ones(n, np.uint8)
+    args = (ptrs, ctypes.c_void_p(0), bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+            w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+            ctypes.c_void_p(0), ctypes.c_void_p(0))
+    assert lib.agc_decode_noalloc(n, 1024, 0, *args) == api.AGC_ESHAPE
+    msg = lib.agc_last_error(None).decode()
+    assert "257" in msg and "256" in msg, msg
+    assert lib.agc_decode_noalloc(0, 1024, 0, *args) == api.AGC_ESHAPE
+    assert lib.agc_decode_noalloc(4, 0, 0, *args) == api.AGC_ESHAPE
+    assert lib.agc_decode_noalloc(4, 1024, 0, *args) == api.AGC_EINVAL      # null scales / estimate
+
+
 def test_phi_coef_balanced():
     rng = np.random.default_rng(0)
     p = rng.uniform(0.05, 0.6, 16)
