@@ -402,6 +402,40 @@ void agc_oracle_codes_range(const float *G, int64_t ldg, const int32_t *row_ptr,
     }
 }
 
+/*
+ * Exact second moments of worker i's message (b >= 2), for the Monte-Carlo checks of the
+ * residual error (proof of Lemma 1, before any bounding):
+ *   *sumsq = sum_m f_i[m]^2                       (enters the straggler term p_i ||f_i||^2)
+ *   *var_q = sum_m Var[Q_i(f_i)_m | f_i]
+ *          = (scale/L)^2 * sum_m pu_m (1 - pu_m)  over coordinates whose cell lies below L,
+ * pu_m being the round-up probability of the rounding rule of Sec. II-B as quantize_prob
+ * returns it (at the top cell the clamp leaves nothing random).  Binary64 sums; the order of
+ * the additions is not fixed (nothing is decided by these values).
+ * Returns 0, or -1 for a one-bit worker (outside the paper; not covered here).
+ */
+int agc_oracle_worker_moments(const float *G, int64_t ldg, const int32_t *row_ptr,
+                              const int32_t *col, const float *val, int i, int bits,
+                              float scale, int64_t d, double *sumsq, double *var_q)
+{
+    if (bits < 2) return -1;
+    float inv16 = agc_oracle_inv16(scale, bits);
+    uint32_t L = (uint32_t)agc_oracle_levels(bits);
+    double unit = (double)scale / (double)L;
+    double ss = 0.0, vq = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : ss, vq)
+    for (int64_t m = 0; m < d; ++m) {
+        float f = agc_oracle_encode_one(G, ldg, row_ptr, col, val, i, m);
+        uint32_t lo;
+        double pu;
+        agc_oracle_quantize_prob(f, inv16, bits, &lo, &pu);
+        ss += (double)f * (double)f;
+        if (lo < L) vq += pu * (1.0 - pu);
+    }
+    *sumsq = ss;
+    *var_q = unit * unit * vq;
+    return 0;
+}
+
 /* encode + quantize + pack for all workers.  scales_in == NULL: scales are
  * computed (and returned in scales_out); otherwise scales_in is used as given
  * and copied to scales_out. */

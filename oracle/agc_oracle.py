@@ -97,6 +97,9 @@ def lib():
                                       _u8p, _f32p, _u8p, C.c_uint64, C.c_uint64, C.c_int,
                                       C.POINTER(_u8p), _f32p, _f32p]
         L.agc_oracle_step.restype = None
+        L.agc_oracle_worker_moments.argtypes = [_f32p, C.c_int64, _i32p, _i32p, _f32p, C.c_int, C.c_int, C.c_float,
+                                                C.c_int64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.agc_oracle_worker_moments.restype = C.c_int
         L.agc_oracle_threads.argtypes = []
         L.agc_oracle_threads.restype = C.c_int
     return _lib
@@ -377,6 +380,18 @@ def codes_range(G, csr, i, bits_i, scale_i, seed, step, m0, m1):
                                  float(np.float32(scale_i)), int(seed), int(step), int(m0), int(m1),
                                  out.ctypes.data_as(_u32p))
     return out
+
+
+def worker_moments(G, csr, i, bits_i, scale_i):
+    """(sum_m f_i[m]^2, sum_m Var[Q_i(f_i)_m]) in binary64 over all coordinates (b >= 2)."""
+    G, gp = _f32(G)
+    rp, cp, vp = csr.ptrs()
+    ss, vq = C.c_double(), C.c_double()
+    rc = lib().agc_oracle_worker_moments(gp, G.strides[0] // 4, rp, cp, vp, int(i), int(bits_i),
+                                         float(np.float32(scale_i)), G.shape[1], C.byref(ss), C.byref(vq))
+    if rc != 0:
+        raise ValueError("worker_moments covers b >= 2 only")
+    return float(ss.value), float(vq.value)
 
 
 def encode_quantize(G, csr, bits, seed, step, scale_mode, scales_in=None):

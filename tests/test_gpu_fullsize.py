@@ -15,15 +15,29 @@ pytestmark = pytest.mark.gpu
 WINDOW = 4096
 
 
-def _problem(cfg):
+def _problem(cfg, code_kind="cyclic"):
+    """code_kind "cyclic": the configurations' cyclic support with column-normalised weights;
+    "interval": the paper's own construction (Theorem 1 targets + interval overlaps, Sec. III-A)."""
     p = I.straggler_probs(cfg)
     bits = I.random_bits(cfg)
     if bits is None:
         z_tot = cfg.bits_law[1] * cfg.n
         bits = api.agc_alloc_bits(p, api.agc_phi_coef_balanced(p, z_tot), z_tot, 2, 8)
     pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
-    row_ptr, col, val, w = api.agc_build_cyclic_code(cfg.n, cfg.k, cfg.s, p, np.maximum(bits, 2), pc)
+    if code_kind == "interval":
+        row_ptr, col, val, w = api.agc_build_code(cfg.n, cfg.k, p, np.maximum(bits, 2), pc)
+        assert len(col) <= cfg.n + cfg.k - 1
+    else:
+        row_ptr, col, val, w = api.agc_build_cyclic_code(cfg.n, cfg.k, cfg.s, p, np.maximum(bits, 2), pc)
     return p, bits, (row_ptr, col, val), w
+
+
+def _expected_path(cfg, code, code_kind):
+    """cyclic band: s; interval construction: 100 + the window (2, 4 or 8) that holds its longest row"""
+    if code_kind == "cyclic":
+        return cfg.s
+    longest = int(np.max(np.diff(code[0])))
+    return 100 + (2 if longest <= 2 else 4 if longest <= 4 else 8)
 
 
 def _windows(cfg, count, rng):
@@ -35,20 +49,24 @@ def _windows(cfg, count, rng):
     return sorted(starts)
 
 
-@pytest.mark.parametrize("name,scale_mode,nwin", [
-    ("resnet50", api.AGC_SCALE_MAXABS, 64),
-    ("resnet50", api.AGC_SCALE_L2, 16),
-    ("resnet18", api.AGC_SCALE_MAXABS, 64),
+@pytest.mark.parametrize("name,code_kind,scale_mode,nwin", [
+    ("resnet50", "cyclic", api.AGC_SCALE_MAXABS, 64),
+    ("resnet50", "cyclic", api.AGC_SCALE_L2, 16),
+    ("resnet18", "cyclic", api.AGC_SCALE_MAXABS, 64),
+    ("resnet50", "interval", api.AGC_SCALE_MAXABS, 48),     # window drivers, rows beyond byte 2^32 of G
+    ("resnet50", "interval", api.AGC_SCALE_L2, 16),
 ])
-def test_full_size_sampled_parity(name, scale_mode, nwin):
+def test_full_size_sampled_parity(name, code_kind, scale_mode, nwin):
     import torch
     cfg = I.CONFIGS[name]
-    p, bits, code, w = _problem(cfg)
+    p, bits, code, w = _problem(cfg, code_kind)
     n, k, d = cfg.n, cfg.k, cfg.d
     G = I.partial_gradients_torch(cfg, torch.device("cuda:0"))
     ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit)
     ctx.agc_set_code(*code)
-    assert ctx.agc_code_path() == cfg.s
+    assert ctx.agc_code_path() == _expected_path(cfg, code, code_kind)
+    if name == "resnet50" and code_kind == "interval":
+        assert ctx.agc_code_path() == 108 and (k - 1) * d * 4 > (1 << 32)
     codes, scales, ghat = ctx.alloc_outputs(bits)
     for c in codes:
         c.fill_(0xA5)
@@ -120,21 +138,24 @@ def test_full_size_sampled_parity(name, scale_mode, nwin):
     ctx.close()
 
 
-@pytest.mark.parametrize("name,scale_mode,nwin", [
-    ("resnet50", api.AGC_SCALE_MAXABS, 48),
-    ("resnet18", api.AGC_SCALE_L2, 16),
+@pytest.mark.parametrize("name,code_kind,scale_mode,nwin", [
+    ("resnet50", "cyclic", api.AGC_SCALE_MAXABS, 48),
+    ("resnet18", "cyclic", api.AGC_SCALE_L2, 16),
+    ("resnet50", "cyclic", api.AGC_SCALE_L2, 48),
+    ("resnet50", "interval", api.AGC_SCALE_MAXABS, 48),
 ])
-def test_full_size_bucket_scales_sampled_parity(name, scale_mode, nwin):
+def test_full_size_bucket_scales_sampled_parity(name, code_kind, scale_mode, nwin):
     """The bucket-wise path (one scale per 256 coordinates, single fused pass) at full size:
     every scale of every worker inside the sampled windows, every code there and the estimate,
     against the oracle; determinism; stream padding."""
     import torch
     cfg = I.CONFIGS[name]
-    p, bits, code, w = _problem(cfg)
+    p, bits, code, w = _problem(cfg, code_kind)
     n, k, d = cfg.n, cfg.k, cfg.d
     G = I.partial_gradients_torch(cfg, torch.device("cuda:0"))
     ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=256)
     ctx.agc_set_code(*code)
+    assert ctx.agc_code_path() == _expected_path(cfg, code, code_kind)
     codes, scales, ghat = ctx.alloc_outputs(bits)
     for c in codes:
         c.fill_(0xA5)

@@ -41,6 +41,37 @@ def _exact_error(cfg, G, csr, bits, w, p, scale_mode):
 
 
 @pytest.mark.parametrize("scale_mode", [O.SCALE_MAXABS, O.SCALE_L2])
+def test_worker_moments_equal_the_per_coordinate_sums(scale_mode):
+    """The whole-vector moment routine used by the large Monte-Carlo checks against a plain
+    loop over the per-coordinate round-up probabilities (themselves pinned by brute force over
+    all primary fields), and against a direct variance of the two-point outcome of every
+    coordinate; the clamp case (|f| = scale has no randomness) is part of the max-abs run."""
+    cfg, p, bits, csr, w, G = _setup(scale_mode)
+    scales = O.scales(G, csr, scale_mode)
+    for i in range(cfg.n):
+        b = int(bits[i])
+        f = O.encode(G, csr, i)
+        inv, L = O.inv16(scales[i], b), O.levels(b)
+        unit = float(scales[i]) / L
+        m0 = min(max(0, int(np.argmax(np.abs(f))) - 100), cfg.d - 1500)   # the window holds |f| = max|f|
+        win = f[m0:m0 + 1500]
+        tot, clamped = 0.0, 0
+        for x in win:
+            lo, pu = O.quantize_prob(x, inv, b)
+            up = min(lo + 1, L)
+            clamped += lo >= L
+            mean = unit * ((1 - pu) * lo + pu * up)
+            tot += (1 - pu) * (unit * lo - mean) ** 2 + pu * (unit * up - mean) ** 2
+        if scale_mode == O.SCALE_MAXABS:
+            assert clamped >= 1
+        ss, vq = O.worker_moments(G[:, m0:m0 + 1500], csr, i, b, scales[i])
+        assert ss == pytest.approx(float(np.sum(win.astype(np.float64) ** 2)), rel=1e-13)
+        assert vq == pytest.approx(tot, rel=1e-11)
+    with pytest.raises(ValueError):
+        O.worker_moments(G, csr, 0, 1, 1.0)
+
+
+@pytest.mark.parametrize("scale_mode", [O.SCALE_MAXABS, O.SCALE_L2])
 def test_montecarlo_unbiased_and_residual(scale_mode):
     cfg, p, bits, csr, w, G = _setup(scale_mode)
     T = cfg.iters
