@@ -29,6 +29,7 @@ struct agc_ctx {
     agc_opts opts{};
     int device = 0;
     // code matrix
+    bool slots_dirty = false;  // a scale pass may have run without its finalize (a launch failed in between)
     bool has_code = false;
     int nnz = 0;
     int* d_row_ptr = nullptr;
@@ -202,13 +203,11 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     c->ws.nseg = (nblocks + 3) / 4;
     c->ws.ngroup = (c->ws.nseg + 63) / 64;
     c->ws.nsuper = (c->ws.ngroup + 63) / 64;
-    c->ws.nblk = nblocks;
-    c->ws.nchunk = (nblocks + agc::kMaxChunkBlocks - 1) / agc::kMaxChunkBlocks;
     if (o.bucket) {
         e = dev_alloc(&c->ws.srow, (size_t)n);  // the scales need no reduction workspace
     } else if (o.scale_mode == AGC_SCALE_MAXABS) {
-        e = dev_alloc(&c->ws.part_max, (size_t)c->ws.nblk * n);
-        if (e == hipSuccess) e = dev_alloc(&c->ws.part_max2, (size_t)c->ws.nchunk * n);
+        e = dev_alloc(&c->ws.part_max, (size_t)agc::kMaxSlots * n);
+        if (e == hipSuccess) e = hipMemset(c->ws.part_max, 0, sizeof(uint32_t) * (size_t)agc::kMaxSlots * n);
     } else {
         e = dev_alloc(&c->ws.part_sq, (size_t)c->ws.nseg * n);
         if (e == hipSuccess) e = dev_alloc(&c->ws.group_sq, (size_t)c->ws.ngroup * n);
@@ -231,7 +230,6 @@ void agc_destroy(agc_ctx* c)
     if (!c) return;
     free_code(c);
     if (c->ws.part_max) (void)hipFree(c->ws.part_max);
-    if (c->ws.part_max2) (void)hipFree(c->ws.part_max2);
     if (c->ws.part_sq) (void)hipFree(c->ws.part_sq);
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
     if (c->ws.super_sq) (void)hipFree(c->ws.super_sq);
@@ -365,9 +363,16 @@ agc_status encode_quantize_impl(agc_ctx* c, const float* G, int64_t ldg, const u
         if (e != hipSuccess) return hip_fail(c, e, "bucket-wise quantize launch");
         return t.end();
     }
+    const bool maxabs = c->opts.scale_mode == AGC_SCALE_MAXABS;
+    if (maxabs && c->slots_dirty) {  // the finalize hands the running maxima back zeroed; restore that after a failure
+        e = agc::launch_scale_clear_slots(c->n, c->ws, stream);
+        if (e != hipSuccess) return hip_fail(c, e, "clearing the scale workspace");
+        c->slots_dirty = false;
+    }
     {
         KernelTimer t{c, 0, stream};
         if ((st = t.begin()) != AGC_OK) return st;
+        c->slots_dirty = maxabs;
         e = agc::launch_scale_pass(G, ldg, c->n, c->k, c->d, code, c->opts.scale_mode, c->ws, stream);
         if (e != hipSuccess) return hip_fail(c, e, "scale pass launch");
         if ((st = t.end()) != AGC_OK) return st;
@@ -377,6 +382,7 @@ agc_status encode_quantize_impl(agc_ctx* c, const float* G, int64_t ldg, const u
         if ((st = t.begin()) != AGC_OK) return st;
         e = agc::launch_scale_finalize(c->n, c->opts.scale_mode, qs, sw, c->ws, scales, stream);
         if (e != hipSuccess) return hip_fail(c, e, "scale finalize launch");
+        c->slots_dirty = false;
         if ((st = t.end()) != AGC_OK) return st;
     }
     {

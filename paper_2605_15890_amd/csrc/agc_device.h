@@ -203,11 +203,14 @@ struct RingShapeT {
     static constexpr int R = S + P;
     static constexpr int NSTASH = S > 1 ? S - 1 : 1;
 };
+// The prefetch distance is a property of the epilogue (Epi::kPrefetchRows): the scale pass has
+// registers to spare and keeps many rows in flight, the quantize pass does not.
 #ifndef AGC_PREFETCH_ROWS
 #define AGC_PREFETCH_ROWS 4
 #endif
-template <int S>
-using RingShape = RingShapeT<S, AGC_PREFETCH_ROWS>;
+#ifndef AGC_SCALE_PREFETCH_ROWS
+#define AGC_SCALE_PREFETCH_ROWS 4
+#endif
 
 // value select (the operands are read before the choice, so the choice is between registers)
 __device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)
@@ -216,21 +219,21 @@ __device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)
 }
 
 // stash helpers with compile-time indices (so the stash stays in registers)
-template <int S, int... Us>
-__device__ __forceinline__ float4 stash_pick(const float4 (&stash)[RingShape<S>::NSTASH], int idx,
+template <int S, int PF, int... Us>
+__device__ __forceinline__ float4 stash_pick(const float4 (&stash)[(RingShapeT<S, PF>::NSTASH)], int idx,
                                              std::integer_sequence<int, Us...>)
 {
     float4 v = stash[0];
-    ((v = sel4(idx == Us + 1, stash[(Us + 1) < RingShape<S>::NSTASH ? (Us + 1) : 0], v)), ...);
+    ((v = sel4(idx == Us + 1, stash[(Us + 1) < RingShapeT<S, PF>::NSTASH ? (Us + 1) : 0], v)), ...);
     return v;
 }
 
-template <int S, int r, int... Us>
-__device__ __forceinline__ void stash_fill(float4 (&stash)[RingShape<S>::NSTASH],
-                                           const float4 (&ring)[RingShape<S>::R],
+template <int S, int PF, int r, int... Us>
+__device__ __forceinline__ void stash_fill(float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
+                                           const float4 (&ring)[(RingShapeT<S, PF>::R)],
                                            std::integer_sequence<int, Us...>)
 {
-    constexpr int R = RingShape<S>::R;
+    constexpr int R = RingShapeT<S, PF>::R;
     ((stash[Us] = ring[(r + R - (S - 1) + Us) % R]), ...);
 }
 
@@ -239,15 +242,15 @@ __device__ __forceinline__ void stash_fill(float4 (&stash)[RingShape<S>::NSTASH]
 // is valid and no wrapped row is involved, so the compiler can count outstanding loads exactly
 // and let P of them stay in flight.  The first round and the last one or two (GENERAL) carry
 // the conditions: workers that do not exist yet, the stash fill, the wrapped rows.
-template <int S, int r, bool STEADY, class Epi>
-__device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
-                                          float4 (&stash)[RingShape<S>::NSTASH],
+template <int S, int PF, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)],
+                                          float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                           const float*& next_row, int64_t ldg, int k,
                                           const float* __restrict__ bval, const LaneCoords& lc,
                                           int j0, Epi& epi)
 {
-    constexpr int P = RingShape<S>::P;
-    constexpr int R = RingShape<S>::R;
+    constexpr int P = RingShapeT<S, PF>::P;
+    constexpr int R = RingShapeT<S, PF>::R;
     const int j = j0 + r;
     if (STEADY) {
         ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
@@ -258,12 +261,12 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
             next_row += (j + P + 1 < k) ? ldg : 0;
         }
         if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
-            ring[r] = stash_pick<S>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
+            ring[r] = stash_pick<S, PF>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
     }
     const int i = j - (S - 1);
     if (STEADY || (i >= 0 && i < k)) {
         if (!STEADY && S > 1 && i == 0)
-            stash_fill<S, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
+            stash_fill<S, PF, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
         const float* bv = bval + (int64_t)i * S;
         float4 f = mul4(bv[0], ring[(r + R - (S - 1)) % R]);
 #pragma unroll
@@ -272,28 +275,28 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[RingShape<S>::R],
     }
 }
 
-template <int S, bool STEADY, class Epi, int... Rs>
-__device__ __forceinline__ void ring_round(float4 (&ring)[RingShape<S>::R],
-                                           float4 (&stash)[RingShape<S>::NSTASH],
+template <int S, int PF, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void ring_round(float4 (&ring)[(RingShapeT<S, PF>::R)],
+                                           float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                            const float*& next_row, int64_t ldg, int k,
                                            const float* __restrict__ bval, const LaneCoords& lc,
                                            int j0, Epi& epi, std::integer_sequence<int, Rs...>)
 {
-    (ring_step<S, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, epi), ...);
+    (ring_step<S, PF, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, epi), ...);
 }
 
-template <int S, class Epi>
+template <int S, int PF, class Epi>
 __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t ldg, int k,
                                             const float* __restrict__ bval, const LaneCoords& lc,
                                             Epi& epi)
 {
-    constexpr int P = RingShape<S>::P;
-    constexpr int R = RingShape<S>::R;
+    constexpr int P = RingShapeT<S, PF>::P;
+    constexpr int R = RingShapeT<S, PF>::R;
     static_assert(R % 2 == 0, "ring length must be even");
     constexpr auto seq = std::make_integer_sequence<int, R>{};
     const int steps = k + S - 1;  // row arrivals, the last S-1 being the wrapped rows
     float4 ring[R];
-    float4 stash[RingShape<S>::NSTASH];
+    float4 stash[(RingShapeT<S, PF>::NSTASH)];
     const float* next_row = G;  // G already points at the block's first coordinate in row 0
 #pragma unroll
     for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -306,11 +309,11 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
         }
     }
     int j0 = 0;
-    ring_round<S, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+    ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
     for (j0 = R; j0 + R - 1 < k; j0 += R)
-        ring_round<S, true>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, PF, true>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
     for (; j0 < steps; j0 += R)
-        ring_round<S, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -397,13 +400,13 @@ __device__ __forceinline__ WindowCur load_window_rec(const WindowRec* rec)
     return c;
 }
 
-template <int W, int r, bool STEADY, class Epi>
-__device__ __forceinline__ void window_step(float4 (&ring)[RingShape<W>::R], const float*& next_row,
+template <int W, int PF, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void window_step(float4 (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
                                             int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
                                             int j0, int& i, WindowCur& cur, Epi& epi)
 {
-    constexpr int P = RingShape<W>::P;
-    constexpr int R = RingShape<W>::R;
+    constexpr int P = RingShapeT<W, PF>::P;
+    constexpr int R = RingShapeT<W, PF>::R;
     const int j = j0 + r;
     if (STEADY || j + P < k) {  // prefetch the row that arrives P steps from now
         ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
@@ -422,21 +425,21 @@ __device__ __forceinline__ void window_step(float4 (&ring)[RingShape<W>::R], con
     }
 }
 
-template <int W, bool STEADY, class Epi, int... Rs>
-__device__ __forceinline__ void window_round(float4 (&ring)[RingShape<W>::R], const float*& next_row,
+template <int W, int PF, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void window_round(float4 (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
                                              int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
                                              int j0, int& i, WindowCur& cur, Epi& epi,
                                              std::integer_sequence<int, Rs...>)
 {
-    (window_step<W, Rs, STEADY>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi), ...);
+    (window_step<W, PF, Rs, STEADY>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi), ...);
 }
 
-template <int W, class Epi>
+template <int W, int PF, class Epi>
 __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64_t ldg, int k,
                                               const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
-    constexpr int P = RingShape<W>::P;
-    constexpr int R = RingShape<W>::R;
+    constexpr int P = RingShapeT<W, PF>::P;
+    constexpr int R = RingShapeT<W, PF>::R;
     constexpr auto seq = std::make_integer_sequence<int, R>{};
     float4 ring[R];
     const float* next_row = G;
@@ -454,9 +457,9 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
     int j0 = 0;
     const int steps = k + W - 1;  // the last worker may be anchored at row k-1
     for (; j0 + R - 1 + P < k; j0 += R)  // every prefetch of the round exists
-        window_round<W, true>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
+        window_round<W, PF, true>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
     for (; j0 < steps; j0 += R)
-        window_round<W, false>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
+        window_round<W, PF, false>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
 }
 
 // The same driver for epilogues that store inside the worker loop (the quantize pass).  Stores
@@ -559,12 +562,12 @@ __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_
                                              const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     if constexpr (S > 0) {
-        if (!lc.wave_ragged) encode_ring<S>(G, ldg, k, B.val, lc, epi);
+        if (!lc.wave_ragged) encode_ring<S, Epi::kPrefetchRows>(G, ldg, k, B.val, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);
     } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
         if (lc.wave_ragged) encode_gather<true>(G, ldg, n, B, lc, epi);
         else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, k, B, lc, epi);
-        else encode_window<-S>(G, ldg, k, B, lc, epi);
+        else encode_window<-S, Epi::kPrefetchRows>(G, ldg, k, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);

@@ -50,8 +50,7 @@ struct WorkerD {
 };
 
 struct Workspace {
-    uint32_t* part_max;   // [nblk][n]   per-block max |f_i| as bit patterns    (max-abs scale)
-    uint32_t* part_max2;  // [n][nchunk] the same, reduced over chunks of kMaxChunkBlocks blocks
+    uint32_t* part_max;   // [kMaxSlots][n] running max |f_i| as bit patterns, all zero between steps (max-abs scale)
     double* part_sq;      // [n][nseg]   per-segment sum of squares             (Euclidean scale)
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
@@ -60,10 +59,9 @@ struct Workspace {
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker
     int64_t nseg, ngroup, nsuper;
-    int64_t nblk, nchunk;
 };
 
-constexpr int kMaxChunkBlocks = 512;  // blocks per chunk of the max-abs reduction
+constexpr int kMaxSlots = 256;  // rows of the max-abs array; a block folds into row (block mod kMaxSlots)
 
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];
@@ -93,6 +91,8 @@ struct DecodeSecond {      // second decoding vector of the two-track decode (Se
 hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t d,
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream);
+// all rows of the max-abs slot array back to zero
+hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stream);
 // K1f: partials -> scales[n] and the per-worker table of the quantize pass.
 // sw.fuse != 0: the quantize pass that follows also forms the estimate (ghat) from the codes it
 // has just produced, in the same order and arithmetic as the decode kernel.

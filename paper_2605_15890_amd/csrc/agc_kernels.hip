@@ -44,6 +44,7 @@ typedef __attribute__((address_space(1))) uint32_t global_word;
 // epilogue for the largest-magnitude scale: exact and order-free
 struct EpiMaxAbs {
     static constexpr bool kStoresPerWorker = false;
+    static constexpr int kPrefetchRows = AGC_SCALE_PREFETCH_ROWS;
     uint32_t* acc;  // this wave's LDS slice [n], bit patterns of non-negative floats
     int lane;
     template <bool EVEN>
@@ -60,6 +61,7 @@ struct EpiMaxAbs {
 // (x0^2+x1^2)+(x2^2+x3^2); exchange-add across the 64 lanes)
 struct EpiSumSq {
     static constexpr bool kStoresPerWorker = false;
+    static constexpr int kPrefetchRows = AGC_SCALE_PREFETCH_ROWS;
     double* acc;  // this wave's LDS slice [n]
     int lane;
     template <bool EVEN>
@@ -77,9 +79,12 @@ struct EpiSumSq {
 // One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it.
 // Euclidean scale: the four block values of every worker meet in LDS and are combined in block
 // order (level 2 of the tree), which keeps the result independent of how the waves were
-// scheduled.  Max-abs scale: the maximum is order-free, so every wave stores its own block's
-// values ([block][worker], one coalesced store) and leaves without waiting for the other
-// waves - the barrier alone cost 4 % of the pass.
+// scheduled.  Max-abs scale: the maximum is exact and order-free, so every wave folds its block's
+// n maxima into one of kMaxSlots rows of a small array ([slot][worker], slot = block mod
+// kMaxSlots) with one integer atomic-max instruction (bit patterns of non-negative floats order
+// like the floats) and leaves; nothing waits, and the pass writes no partial results to memory
+// (stores mixed into the read stream cost far more than their bytes on this memory system).
+// The finalize kernel reads the rows and hands them back zeroed.
 template <int S, int MODE>
 __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restrict__ G,
                                                            const int* __restrict__ row_ptr,
@@ -115,8 +120,9 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
     if (MODE == 1) {
         if (base < a.d) {
             const int64_t blk = seg * kSegBlocks + wave;
-            global_word* dst = (global_word*)a.part_max + blk * a.n;
-            for (int i = lane; i < a.n; i += kWave) dst[i] = accu[i];  // written by this wave's lane 0
+            uint32_t* dst = a.part_max + (blk & (kMaxSlots - 1)) * a.n;
+            for (int i = lane; i < a.n; i += kWave)  // accu[i] was written by this wave's lane 0
+                (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         return;
     }
@@ -131,36 +137,20 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_pass(const float* __restri
     }
 }
 
-// max-abs scale, first reduction: [block][worker] -> [worker][chunk of kMaxChunkBlocks blocks].
-// grid (chunks, ceil(n/64)); lane l of every wave follows worker 64*blockIdx.y + l through the
-// chunk's rows (one coalesced 4n-byte row per step), the four waves take every fourth row.
-__global__ __launch_bounds__(kWgThreads) void k_scale_reduce_max(int n, Workspace ws)
+// rows of the max-abs slot array back to zero (context creation does it with a memset; this
+// kernel serves a call that follows one whose launches failed half-way)
+__global__ __launch_bounds__(kWgThreads) void k_scale_clear_slots(uint32_t* slots, int count)
 {
-    __shared__ uint32_t red[kWavesPerWg][kWave];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int i = (int)blockIdx.y * kWave + lane;
-    const int64_t b0 = (int64_t)blockIdx.x * kMaxChunkBlocks;
-    const int64_t b1 = b0 + kMaxChunkBlocks < ws.nblk ? b0 + kMaxChunkBlocks : ws.nblk;
-    uint32_t m = 0u;
-    if (i < n) {
-        const uint32_t* col = ws.part_max + i;
-        for (int64_t blk = b0 + wave; blk < b1; blk += 8 * kWavesPerWg) {
-            uint32_t v[8];  // eight independent loads in flight per lane
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t bb = blk + (int64_t)u * kWavesPerWg;
-                v[u] = bb < b1 ? col[bb * n] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) m = max(m, v[u]);
-        }
-    }
-    red[wave][lane] = m;
-    __syncthreads();
-    if (wave == 0 && i < n) {
-        m = max(max(red[0][lane], red[1][lane]), max(red[2][lane], red[3][lane]));
-        ws.part_max2[(int64_t)i * ws.nchunk + blockIdx.x] = m;
-    }
+    const int t = blockIdx.x * kWgThreads + threadIdx.x;
+    if (t < count) slots[t] = 0u;
+}
+
+hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stream)
+{
+    const int count = n * kMaxSlots;
+    hipLaunchKernelGGL(k_scale_clear_slots, dim3((count + kWgThreads - 1) / kWgThreads), dim3(kWgThreads), 0, stream,
+                       ws.part_max, count);
+    return hipGetLastError();
 }
 
 template <int S>
@@ -219,17 +209,13 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     __shared__ uint32_t red[kWgThreads];
     float scale;
     if (MODE == 1) {
+        // this worker's column of the slot array: read it with loads that see the atomics of the
+        // scale pass (they were performed in memory, past the caches), and leave zeros behind
         uint32_t m = 0u;
-        const uint32_t* part = ws.part_max2 + (int64_t)i * ws.nchunk;
-        for (int64_t s0 = tid; s0 < ws.nchunk; s0 += 8 * kWgThreads) {
-            uint32_t v[8];  // eight independent loads in flight per lane
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t s = s0 + (int64_t)u * kWgThreads;
-                v[u] = s < ws.nchunk ? part[s] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) m = max(m, v[u]);
+        for (int sl = tid; sl < kMaxSlots; sl += kWgThreads) {
+            uint32_t* p = ws.part_max + (int64_t)sl * n + i;
+            m = max(m, __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         red[tid] = m;
         __syncthreads();
@@ -288,15 +274,10 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
 hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
-    if (scale_mode == 0) {
+    if (scale_mode == 0)
         hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
-    } else {
-        hipLaunchKernelGGL(k_scale_reduce_max, dim3((unsigned)ws.nchunk, (unsigned)((n + kWave - 1) / kWave)),
-                           dim3(kWgThreads), 0, stream, n, ws);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+    else
         hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
-    }
     return hipGetLastError();
 }
 

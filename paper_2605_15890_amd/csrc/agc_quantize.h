@@ -24,7 +24,14 @@ struct QuantArgs {
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
 
-constexpr int kStageWords = 8 * 16 + 4;  // 256 codes of up to 16 bits, plus spill of zero bits; 16-byte multiple
+constexpr int kStageWords = 64 * 4 + 4;  // 16 bytes per lane (256 codes of up to 16 bits fill half), plus spill of zero bits
+// raw buffer descriptor, last word: 32-bit untyped data format of this target; the bounds check is
+// on the byte offset against num_records (stride 0)
+constexpr int kBufferRsrcFlags = 0x00020000;
+#ifndef AGC_PAYLOAD_POLICY
+#define AGC_PAYLOAD_POLICY 2
+#endif
+constexpr int kBufferNonTemporal = AGC_PAYLOAD_POLICY;  // cache-policy operand: 2 = the non-temporal bit
 
 // One rounding decision (Sec. II-B): T is the grid position scaled by 2^16; the cell is
 // T >> 16, the low 16 bits are the first 16 bits of the round-up probability, compared with
@@ -73,10 +80,12 @@ __device__ __forceinline__ void wave_lds_fence()
 template <int BUCKET, bool FUSE>
 struct EpiQuant {
     static constexpr bool kStoresPerWorker = true;  // the payload leaves inside the worker loop
+    static constexpr int kPrefetchRows = AGC_PREFETCH_ROWS;
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
     uint32_t* stage;     // this wave's LDS staging words, all zero between workers
     int lane;
+    uint32_t lane_byte16;  // 16 * lane
     int64_t block;       // index of this wave's 256-coordinate block
     int groups_valid;    // 128-code groups of this block that exist in the streams (1 or 2)
     uint32_t ctr0;       // m >> 2 of this lane's coordinates
@@ -229,16 +238,25 @@ struct EpiQuant {
         // (16 bytes per lane: 2b lanes cover the 8b words; the payload is not read again, so the
         // store is non-temporal)
         typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-        if (lane < 2 * b) {
-            u32x4_t* sp = reinterpret_cast<u32x4_t*>(stage) + lane;
-            const u32x4_t v = *sp;
-            *sp = u32x4_t{0u, 0u, 0u, 0u};
-            if (lane < b * groups_valid) {
-                __attribute__((address_space(1))) u32x4_t* dst =
-                    (__attribute__((address_space(1))) u32x4_t*)q.codes + (block * (2 * b) + lane);
-                __builtin_nontemporal_store(v, dst);
-            }
-        }
+        // Read-out and store run for all 64 lanes without a branch: every lane hands its 16 staged
+        // bytes over (lanes past the block's 2b pieces hold zeros and hand zeros back), and the
+        // store goes through a buffer descriptor that covers exactly this block's bytes of the
+        // stream, so the hardware's range check drops the lanes beyond it.  Behind a branch that
+        // may skip the store the compiler cannot count outstanding memory operations, and every
+        // wait for a row of G then also waits for the most recent stores.
+        u32x4_t* sp = reinterpret_cast<u32x4_t*>(stage) + lane;
+        const u32x4_t v = *sp;
+        *sp = u32x4_t{0u, 0u, 0u, 0u};
+        const uint32_t piece_bytes = 16u * (uint32_t)b;                      // 128 codes
+        // the block's first byte in the stream is wave-uniform: say so, so that the descriptor
+        // lives in scalar registers on every path
+        const uint64_t dst_bits = (uint64_t)q.codes + (uint64_t)block * (2u * piece_bytes);
+        const uint32_t dst_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dst_bits);  // the builtin returns int:
+        const uint32_t dst_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dst_bits >> 32));  // widen as unsigned
+        char* blk_dst = (char*)(((uint64_t)dst_hi << 32) | (uint64_t)dst_lo);
+        const int blk_bytes = __builtin_amdgcn_readfirstlane((int)(piece_bytes * (uint32_t)groups_valid));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(blk_dst, 0, blk_bytes, kBufferRsrcFlags);
+        __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)lane_byte16, 0, kBufferNonTemporal);
         wave_lds_fence();
     }
 };
@@ -257,21 +275,36 @@ __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(S ==
     __shared__ __attribute__((aligned(16))) uint32_t lds_stage[kWavesPerWg][kStageWords];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
     const int lane = threadIdx.x % kWave;
+#ifdef AGC_XCD_ORDER
+    int64_t wg = blockIdx.x;
+    {
+        const int64_t per = gridDim.x / 8;
+        if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
+    }
+    const int64_t block = wg * kWavesPerWg + wave;
+#else
     const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
+#endif
     const int64_t base = block * (int64_t)kBlockCoords;
     for (int w = lane; w < kStageWords; w += kWave) lds_stage[wave][w] = 0u;
     wave_lds_fence();
     if (base >= a.d) return;
     const LaneCoords lc = lane_coords(base, lane, a.d);
     const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
-    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, block,
+    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, 16u * (uint32_t)lane, block,
                                groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
                                lc.wave_ragged, 0u, 0u, a.scales, a.nb, {0.f, 0.f, 0.f, 0.f}};
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
         if (lc.nvalid == 4) {
+#ifdef AGC_GHAT_NT
+            typedef float f32x4_t __attribute__((ext_vector_type(4)));
+            __builtin_nontemporal_store(f32x4_t{epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]},
+                                        (__attribute__((address_space(1))) f32x4_t*)dst);
+#else
             *reinterpret_cast<float4*>(dst) = make_float4(epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]);
+#endif
         } else {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
