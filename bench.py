@@ -8,7 +8,14 @@ dominant kernel (HIP-event durations measured in the timed region) and the CPU o
 on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--scale maxabs|l2]
-                    [--code cyclic|interval] [--no-cpu-baseline]
+                    [--code cyclic|interval] [--bucket 0|256] [--two-pass] [--no-variants]
+                    [--no-cpu-baseline]
+
+The default run (no flags) times the metric configuration (resnet50-sized: n = k = 64, s = 4,
+d = 25.6 M, cyclic code, max-abs scale per vector, fused step) and then, in the same process and
+on the same inputs, the other forms the library offers at that size (two-pass step, Euclidean
+scale, the paper's interval code, bucket-wise scales), a plain copy and the bare access pattern of
+the two streaming passes, so that every number quoted anywhere comes from one timed line.
 """
 import argparse
 import json
@@ -149,6 +156,134 @@ def bench_lsq(args):
     ctx.close()
 
 
+def tag_of(cfg, code, scale, bucket, two_pass):
+    return (f"{cfg.name}_{code}_{scale}" + (f"_bucket{bucket}" if bucket else "") + ("_two_pass" if two_pass else ""))
+
+
+def alg_bytes_of(n, k, d, bits, masks, bucket, two_pass):
+    """Algorithmic bytes per launch of each kernel: what the method must move."""
+    nb = (d + 255) // 256 if bucket else 0
+    sum_b = float(np.sum(bits))
+    arrived_b = float(np.mean([np.sum(bits[m.astype(bool)]) for m in masks]))
+    n_arr = float(np.mean([m.sum() for m in masks]))
+    return {
+        "scale_pass": 0.0 if bucket else 4.0 * k * d,
+        "scale_finalize": 0.0,
+        "quantize": 4.0 * k * d + d * sum_b / 8.0 + 4.0 * n * nb + (0.0 if two_pass else 4.0 * d),
+        "decode": (d * arrived_b / 8.0 + 4.0 * d + 4.0 * n_arr * nb) if two_pass else 0.0,
+    }
+
+
+def time_variant(api, I, cfg, G, bufs, p, bits, code, w, scale, bucket, two_pass, K, W, seed):
+    """W warm-up steps, K timed steps without any event between the kernels (wall clock bracketed by
+    device synchronisation: this is the step time), then K more steps with a HIP-event pair around
+    every kernel on the stream the kernels run on (their average durations; the event records
+    themselves cost about 20 us per step, which is why the two are separate regions)."""
+    import torch
+    n, k, d = cfg.n, cfg.k, cfg.d
+    scale_mode = api.AGC_SCALE_MAXABS if scale == "maxabs" else api.AGC_SCALE_L2
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=bucket, unfused_step=two_pass)
+    ctx.agc_set_code(*code)
+    codes, ghat = bufs
+    per = ctx.agc_scales_per_worker()
+    scales = torch.empty((n, per) if bucket else n, dtype=torch.float32, device=G.device)
+    masks = [I.arrival_mask(cfg, p, t) for t in range(W + 2 * K)]     # sampled outside the timed regions
+    for t in range(W):
+        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.agc_profile_enable(True)
+    ctx.agc_profile_read()
+    for t in range(W + K, W + 2 * K):
+        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    prof = ctx.agc_profile_read()
+    ctx.agc_profile_enable(False)
+    path = ctx.agc_code_path()
+    ctx.close()
+    del scales
+    ms_per_step = (t1 - t0) * 1e3 / K
+    alg = alg_bytes_of(n, k, d, bits, masks[W:W + K], bucket, two_pass)
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        avg = ms / cnt
+        kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
+                         "alg_GBps": round(alg[name] / (avg * 1e-3) / 1e9, 1) if avg > 0 else None}
+    dominant = max(kernels, key=lambda nm: kernels[nm]["avg_ms"])
+    return {"ms_per_step": ms_per_step, "ms_per_step_with_events": (t2 - t1) * 1e3 / K, "kernels": kernels,
+            "dominant": dominant, "alg": alg, "code_path": path}
+
+
+def roofline_of(r, tag):
+    dom = r["dominant"]
+    dom_avg_s = r["kernels"][dom]["avg_ms"] * 1e-3
+    achieved = r["alg"][dom] / dom_avg_s / 1e9
+    step_alg = sum(r["alg"].values())
+    traffic, traffic_src = stored_traffic(tag, dom)
+    out = {
+        "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
+        "avg_launch_ms": r["kernels"][dom]["avg_ms"], "alg_bytes_per_launch": r["alg"][dom],
+        "step_alg_bytes": step_alg,
+        "step_hbm_frac": round(step_alg / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    valu_ops = stored_valu(tag, dom)
+    if valu_ops:   # the kernel also does plain vector-ALU work: say how close to that peak it runs
+        out["valu"] = {"lane_ops_per_launch": valu_ops,
+                       "achieved_Tlaneops": round(valu_ops / dom_avg_s / 1e12, 2),
+                       "peak_Tlaneops": round(VALU_PEAK_GLANEOPS / 1e3, 2),
+                       "frac": round(valu_ops / dom_avg_s / 1e9 / VALU_PEAK_GLANEOPS, 4)}
+    return out
+
+
+def measured_ceilings(api, G, k, d, scratch):
+    """What this machine's memory system delivers, timed with HIP events on the current stream: a plain
+    copy (1 GiB in, 1 GiB out) and the bare access pattern of the two streaming passes (all of G
+    read row by row as the passes read it; the same plus one 96-byte piece per row and wave written
+    to the row's own output stream, which is what a 3-bit worker's payload looks like)."""
+    import torch
+    out = {}
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best
+
+    nbytes = 1 << 30
+    src = scratch[:nbytes // 4]
+    dst = scratch[nbytes // 4: nbytes // 2]
+    ms = timed(lambda: api.agc_calibration_copy(dst, src, nbytes))
+    out["copy_GBps"] = round(2.0 * nbytes / (ms * 1e-3) / 1e9, 1)
+    g_bytes = 4.0 * k * (d // 256) * 256
+    ms = timed(lambda: api.agc_debug_stream_rows(G, 0, scratch))
+    out["pattern_read_ms"] = round(ms, 4)
+    out["pattern_read_GBps"] = round(g_bytes / (ms * 1e-3) / 1e9, 1)
+    piece = 96
+    ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch))
+    w_bytes = float(k) * (d // 256) * piece
+    out["pattern_read_write_ms"] = round(ms, 4)
+    out["pattern_read_write_GBps"] = round((g_bytes + w_bytes) / (ms * 1e-3) / 1e9, 1)
+    out["pattern_note"] = (f"bare row walk over G ({g_bytes / 1e9:.2f} GB); with writes: plus {w_bytes / 1e9:.3f} GB "
+                           f"in {piece}-byte pieces to {k} streams")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,11 +294,13 @@ def main():
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
     ap.add_argument("--bucket", type=int, default=0, choices=[0, 256],
                     help="256: one scale per 256-coordinate bucket (single pass over G); 0: one per vector")
-    ap.add_argument("--unfused", action="store_true",
+    ap.add_argument("--two-pass", "--unfused", dest="two_pass", action="store_true",
                     help="run the step as two passes (stand-alone decode kernel) instead of the fused pass")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="time only the configuration the flags select (profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-log2", type=int, default=23,
-                    help="the oracle is timed on the first 2^this coordinates (all partitions)")
+    ap.add_argument("--cpu-sample-log2", type=int, default=21,
+                    help="the single-thread oracle leg runs on the first 2^this coordinates")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 1 GiB copy kernel (reference for the traffic counters)")
     args = ap.parse_args()
@@ -183,19 +320,14 @@ def main():
     cfg = I.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    scale_mode = api.AGC_SCALE_MAXABS if args.scale == "maxabs" else api.AGC_SCALE_L2
-    p, bits, code, w = build_problem(cfg, api, args.code)
     n, k, d = cfg.n, cfg.k, cfg.d
-
+    p, bits, code, w = build_problem(cfg, api, args.code)
     G = I.partial_gradients_torch(cfg, dev)
     assert G.stride(0) % 4 == 0 and G.data_ptr() % 16 == 0
-    ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=args.bucket,
-                      unfused_step=args.unfused)
-    ctx.agc_set_code(*code)
-    codes, scales, ghat = ctx.alloc_outputs(bits)
-    nb = ctx.agc_scales_per_worker() if args.bucket else 0
+    codes = [torch.empty(api.agc_code_bytes(d, int(b)), dtype=torch.uint8, device=dev) for b in bits]
+    ghat = torch.empty(d, dtype=torch.float32, device=dev)
+    bufs = (codes, ghat)
     K, W = args.steps, args.warmup
-    masks = [I.arrival_mask(cfg, p, t) for t in range(W + K)]     # sampled outside the timed region
     seed = cfg.philox_seed
 
     if args.calibrate:   # known traffic: reads 2^30 bytes, writes 2^30 bytes
@@ -204,80 +336,82 @@ def main():
         api.agc_calibration_copy(dst, src, 1 << 30)
         torch.cuda.synchronize()
         del src, dst
-    for t in range(W):
-        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
-    torch.cuda.synchronize()
-    ctx.agc_profile_enable(True)
-    ctx.agc_profile_read()
-    t0 = time.perf_counter()
-    for t in range(W, W + K):
-        ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = ctx.agc_profile_read()
-    ctx.agc_profile_enable(False)
 
-    ms_per_step = (t1 - t0) * 1e3 / K
+    main_r = time_variant(api, I, cfg, G, bufs, p, bits, code, w, args.scale, args.bucket, args.two_pass, K, W, seed)
+    ms_per_step = main_r["ms_per_step"]
     grad_bytes = 4.0 * k * d
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+    roofline = roofline_of(main_r, tag_of(cfg, args.code, args.scale, args.bucket, args.two_pass))
 
-    # algorithmic bytes per launch of each kernel (what the method must move)
-    sum_b = float(np.sum(bits))
-    arrived_b = float(np.mean([np.sum(bits[m.astype(bool)]) for m in masks[W:]]))
-    n_arr = float(np.mean([m.sum() for m in masks[W:]]))
-    alg_bytes = {
-        "scale_pass": 0.0 if args.bucket else 4.0 * k * d,
-        "scale_finalize": 0.0,
-        "quantize": 4.0 * k * d + d * sum_b / 8.0 + 4.0 * n * nb + (0.0 if args.unfused else 4.0 * d),
-        "decode": (d * arrived_b / 8.0 + 4.0 * d + 4.0 * n_arr * nb) if args.unfused else 0.0,
-    }
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        if cnt == 0:
-            continue
-        avg = ms / max(cnt, 1)
-        kernels[name] = {"avg_ms": round(avg, 4), "launches": cnt,
-                         "alg_GBps": round(alg_bytes[name] / (avg * 1e-3) / 1e9, 1) if avg > 0 else None}
-    dominant = max(kernels, key=lambda nm: kernels[nm]["avg_ms"])
-    dom_avg_s = kernels[dominant]["avg_ms"] * 1e-3
-    achieved = alg_bytes[dominant] / dom_avg_s / 1e9
-    step_alg_bytes = sum(alg_bytes.values())
-    tag = (f"{cfg.name}_{args.code}_{args.scale}" + (f"_bucket{args.bucket}" if args.bucket else "")
-           + ("_unfused" if args.unfused else ""))
-    traffic, traffic_src = stored_traffic(tag, dominant)
-    roofline = {
-        "kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-        "traffic_source": traffic_src,
-        "avg_launch_ms": kernels[dominant]["avg_ms"],
-        "alg_bytes_per_launch": alg_bytes[dominant],
-        "step_alg_bytes": step_alg_bytes,
-        "step_hbm_frac": round(step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-    }
-    valu_ops = stored_valu(tag, dominant)
-    if valu_ops:   # the kernel is co-bound by plain vector ALU work: say how close to that peak it runs
-        roofline["valu"] = {"lane_ops_per_launch": valu_ops,
-                            "achieved_Tlaneops": round(valu_ops / dom_avg_s / 1e12, 2),
-                            "peak_Tlaneops": round(VALU_PEAK_GLANEOPS / 1e3, 2),
-                            "frac": round(valu_ops / dom_avg_s / 1e9 / VALU_PEAK_GLANEOPS, 4)}
+    default_run = (args.workload == "resnet50" and args.scale == "maxabs" and args.code == "cyclic"
+                   and not args.bucket and not args.two_pass)
+    variants = None
+    if default_run and not args.no_variants:
+        # the other forms of the step at the same size, same process, same inputs
+        Kv = min(K, 20)
+        variants = {}
+        interval = build_problem(cfg, api, "interval")
+        for name, (vcode, vscale, vbucket, vtwo, ckind) in {
+            "two_pass": (code, "maxabs", 0, True, "cyclic"),
+            "l2": (code, "l2", 0, False, "cyclic"),
+            "interval": (interval[2], "maxabs", 0, False, "interval"),
+            "bucket256": (code, "maxabs", 256, False, "cyclic"),
+            "bucket256_l2": (code, "l2", 256, False, "cyclic"),
+            "interval_bucket256": (interval[2], "maxabs", 256, False, "interval"),
+        }.items():
+            vw = interval[3] if ckind == "interval" else w
+            r = time_variant(api, I, cfg, G, bufs, p, bits, vcode, vw, vscale, vbucket, vtwo, Kv, 3, seed)
+            rf = roofline_of(r, tag_of(cfg, ckind, vscale, vbucket, vtwo))
+            variants[name] = {
+                "ms_per_step": round(r["ms_per_step"], 4), "steps": Kv,
+                "value_GBps": round(grad_bytes / (r["ms_per_step"] * 1e-3) / 1e9, 1),
+                "step_alg_bytes": rf["step_alg_bytes"], "step_hbm_frac": rf["step_hbm_frac"],
+                "dominant_kernel": rf["kernel"], "dominant_frac": rf["frac"], "traffic": rf["traffic"],
+                "code_path": r["code_path"],
+                "kernels_avg_ms": {nm: kv["avg_ms"] for nm, kv in r["kernels"].items()},
+            }
+        # what the memory system delivers on this machine: copy and the bare access pattern of the passes
+        scratch = torch.empty(max(1 << 29, k * (d // 256) * 96 // 4 + 4), dtype=torch.float32, device=dev)
+        ceil = measured_ceilings(api, G, k, d, scratch)
+        del scratch
+        roofline["measured_copy_GBps"] = ceil["copy_GBps"]
+        roofline["frac_of_copy"] = round(roofline["achieved"] / ceil["copy_GBps"], 4)
+        roofline["measured_pattern"] = ceil
+        # the dominant kernel against the bare pattern with the same kind of traffic
+        if "pattern_read_write_ms" in ceil and roofline["kernel"] == "quantize":
+            roofline["dominant_vs_bare_pattern"] = round(ceil["pattern_read_write_ms"] / roofline["avg_launch_ms"], 4)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import agc_oracle as O
-        ds = min(d, 1 << args.cpu_sample_log2)
-        Gs = G[:, :ds].contiguous().cpu().numpy()
         csr = O.Csr(code[0], code[1], code[2], k)
-        c0 = time.perf_counter()
         o_mode = O.SCALE_MAXABS if args.scale == "maxabs" else O.SCALE_L2
-        (O.step_bucket if args.bucket else O.step)(Gs, csr, bits, w, masks[W], seed, W, o_mode)
+        o_step = O.step_bucket if args.bucket else O.step
+        mask0 = I.arrival_mask(cfg, p, W)
+        # (i) all threads, one whole step of the workload (every coordinate)
+        Gh = G.cpu().numpy()
+        c0 = time.perf_counter()
+        o_step(Gh, csr, bits, w, mask0, seed, W, o_mode)
         c1 = time.perf_counter()
+        # (ii) one thread, on a bounded sample of the same workload
+        ds = min(d, 1 << args.cpu_sample_log2)
+        Gs = np.ascontiguousarray(Gh[:, :ds])
+        del Gh
+        nthreads = O.threads()
+        O.set_threads(1)
+        s0 = time.perf_counter()
+        o_step(Gs, csr, bits, w, mask0, seed, W, o_mode)
+        s1 = time.perf_counter()
+        O.set_threads(nthreads)
         cpu_baseline = {
-            "value": round(4.0 * k * ds / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": O.threads(),
-            "kind": "oracle",
-            "sample": f"one oracle step on the first {ds} of {d} coordinates of all {k} partitions "
-                      f"({n * ds} coded elements), {c1 - c0:.2f} s wall",
+            "value": round(4.0 * k * d / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"one whole oracle step of the workload (all {d} coordinates of all {k} partitions, "
+                      f"{n * d} coded elements), {c1 - c0:.2f} s wall on {nthreads} threads",
+            "single_thread": {"value": round(4.0 * k * ds / (s1 - s0) / 1e9, 4), "unit": "GB/s", "cores": 1,
+                              "sample": f"one oracle step on the first {ds} coordinates, {s1 - s0:.2f} s wall"},
         }
 
+    sum_b = float(np.sum(bits))
     out = {
         "metric": "encode+quantize+decode GB/s of gradient traffic",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -287,15 +421,20 @@ def main():
                                f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
                                f"{args.code} code, {args.scale} scale"
                                + (f" per {args.bucket}-coordinate bucket" if args.bucket else " per vector")
-                               + (", two-pass step" if args.unfused else ", fused step"),
-                   "code_path": ctx.agc_code_path()},
+                               + (", two-pass step" if args.two_pass else ", fused step"),
+                   "code_path": main_r["code_path"]},
         "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),
+        "timing": {"ms_per_step": "wall clock over the K timed steps, no events between kernels",
+                   "ms_per_step_with_events": round(main_r["ms_per_step_with_events"], 4),
+                   "kernels": "HIP-event pairs around every kernel over K further steps on the same stream"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
-        "kernels": kernels,
+        "kernels": main_r["kernels"],
     }
+    if variants is not None:
+        out["two_pass"] = variants.pop("two_pass")
+        out["variants"] = variants
     print(json.dumps(out))
-    ctx.close()
 
 
 if __name__ == "__main__":

@@ -53,9 +53,8 @@ extern "C" {
 
 #define AGC_MAX_WORKERS 256   /* n <= 256: per-worker arguments travel in the kernel argument block */
 #define AGC_MAX_BITS 16
-#define AGC_NUM_KERNELS 4     /* scale pass, scale finalize, encode+quantize+pack, decode */
 
-typedef struct agc_ctx agc_ctx; /* opaque; owns device workspace, a copy of B and timing events */
+typedef struct agc_ctx agc_ctx; /* opaque; owns device workspace and a copy of B */
 
 typedef enum {
     AGC_OK = 0,
@@ -76,7 +75,7 @@ typedef enum {
 typedef struct {
     int scale_mode;    /* agc_scale_mode */
     int allow_1bit;    /* non-zero: accept b_i = 1 (two-point grid {-scale,+scale}; outside the paper, which needs b >= 2) */
-    int force_generic; /* non-zero: never take the cyclic-band fast path (testing) */
+    int force_generic; /* testing hook (see agc_debug.h): non-zero = every code takes the generic gather path */
     int bucket;        /* 0: one scale per coded vector (the paper's quantizer).  256: one scale per
                           256-coordinate bucket (Sec. II-B names the bucket-wise extension): the
                           scales array becomes n x ceil(d/256) and the worker side reads G once */
@@ -214,19 +213,6 @@ agc_status agc_step(agc_ctx *ctx, const float *G_dev, int64_t ldg, const uint8_t
                     void *const *codes_dev, float *scales_dev, float *ghat_dev, void *hip_stream);
 
 /* --------------------------------------------------------------------------------------
- * Per-kernel timing (HIP events recorded on the caller's stream around each kernel)
- * ------------------------------------------------------------------------------------ */
-/* on != 0: the following hot-path calls bracket each of their kernels with a pair of events
- * (a ring of 128 pairs per kernel; when the ring is full the oldest pair is drained with one
- * event synchronisation).  Kernel indices: 0 scale pass, 1 scale finalize,
- * 2 encode+quantize+pack, 3 decode. */
-agc_status agc_profile_enable(agc_ctx *ctx, int on);
-/* Waits for the recorded events, adds them up and clears the ring: total_ms[j] and
- * launches[j] for each kernel index j since the previous read. */
-agc_status agc_profile_read(agc_ctx *ctx, double total_ms[AGC_NUM_KERNELS],
-                            int64_t launches[AGC_NUM_KERNELS]);
-
-/* --------------------------------------------------------------------------------------
  * End-to-end least-squares loop (the producer of G and the consumer of g_hat)
  * ------------------------------------------------------------------------------------ */
 /* Partial gradients of the least-squares loss 0.5 * ||X_p beta - y_p||^2 of k equal, contiguous
@@ -256,11 +242,6 @@ agc_status agc_gd_update(float *beta_dev, const float *ghat_dev, float lr, int64
 agc_status agc_adam_update(float *beta_dev, float *m1_dev, float *m2_dev, const float *ghat_dev,
                            const float *ghat2_dev, float lr, float beta1, float beta2, float eps,
                            int64_t t, int64_t d, void *hip_stream);
-
-/* Measurement utility, not part of the method: a plain copy kernel that reads `bytes` and
- * writes `bytes` (device pointers, 16-byte aligned, bytes a multiple of 16).  Profiling runs
- * use it as the kernel of known size against which the memory-traffic counters are scaled. */
-agc_status agc_calibration_copy(void *dst_dev, const void *src_dev, int64_t bytes, void *hip_stream);
 
 /* --------------------------------------------------------------------------------------
  * Host-side design routines (no GPU work; run once per change of the system statistics)

@@ -604,6 +604,16 @@ void agc_oracle_step_bucket(int n, int64_t d, const float *G, int64_t ldg,
     }
 }
 
+/* number of threads the parallel loops above may use from now on (timing runs only) */
+void agc_oracle_set_threads(int count)
+{
+#ifdef _OPENMP
+    if (count >= 1) omp_set_num_threads(count);
+#else
+    (void)count;
+#endif
+}
+
 int agc_oracle_threads(void)
 {
 #ifdef _OPENMP

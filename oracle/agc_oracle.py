@@ -100,6 +100,8 @@ def lib():
         L.agc_oracle_worker_moments.argtypes = [_f32p, C.c_int64, _i32p, _i32p, _f32p, C.c_int, C.c_int, C.c_float,
                                                 C.c_int64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.agc_oracle_worker_moments.restype = C.c_int
+        L.agc_oracle_set_threads.argtypes = [C.c_int]
+        L.agc_oracle_set_threads.restype = None
         L.agc_oracle_threads.argtypes = []
         L.agc_oracle_threads.restype = C.c_int
     return _lib
@@ -201,6 +203,10 @@ def step_bucket(G, csr, bits, w, mask, seed, step_, scale_mode):
 
 def threads():
     return int(lib().agc_oracle_threads())
+
+
+def set_threads(count):
+    lib().agc_oracle_set_threads(int(count))
 
 
 def philox4x32_10(ctr, key):

@@ -22,7 +22,7 @@ EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
     "agc_scales_per_worker", "agc_decode2", "agc_decode_noalloc", "agc_adam_update", "agc_second_moment_decoder",
-    "agc_calibration_copy", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
+    "agc_calibration_copy", "agc_debug_stream_rows", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_build_cyclic_code_opt", "agc_check_unbiased",
 ]
@@ -102,6 +102,8 @@ def load():
     L.agc_gd_update.restype = C.c_int
     L.agc_calibration_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
     L.agc_calibration_copy.restype = C.c_int
+    L.agc_debug_stream_rows.argtypes = [_vp, C.c_int64, C.c_int, C.c_int64, C.c_int, _vp, _vp]
+    L.agc_debug_stream_rows.restype = C.c_int
     L.agc_profile_enable.argtypes = [_vp, C.c_int]
     L.agc_profile_enable.restype = C.c_int
     L.agc_profile_read.argtypes = [_vp, _f64p, C.POINTER(C.c_int64)]
@@ -449,6 +451,18 @@ def agc_calibration_copy(dst, src, nbytes, stream=None):
                                      _stream_handle(stream))
     if st != AGC_OK:
         raise AgcError(st, "agc_calibration_copy")
+
+
+def agc_debug_stream_rows(G, piece_bytes, out, stream=None):
+    """The bare access pattern of the streaming passes over G (k x d view); piece_bytes = 0 reads only."""
+    k, d = int(G.shape[0]), int(G.shape[1])
+    need = max(16, k * (d // 256) * int(piece_bytes))
+    if G.dim() != 2 or G.stride(1) != 1 or out.numel() * out.element_size() < need:
+        raise AgcError(AGC_ESHAPE, f"agc_debug_stream_rows: out must hold {need} bytes")
+    st = load().agc_debug_stream_rows(C.c_void_p(G.data_ptr()), G.stride(0), k, d, int(piece_bytes),
+                                      C.c_void_p(out.data_ptr()), _stream_handle(stream))
+    if st != AGC_OK:
+        raise AgcError(st, "agc_debug_stream_rows")
 
 
 def padded_rows(k, d, device="cuda"):

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagc.so")
 SOURCES = ["agc_kernels.hip", "agc_quantize_b0.hip", "agc_quantize_b1.hip", "agc_quantize_b2.hip",
-           "agc_ls_kernels.hip", "agc_api.cpp", "agc_host.cpp"]
+           "agc_ls_kernels.hip", "agc_debug.hip", "agc_api.cpp", "agc_host.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 OBJ_DIR = os.path.join(HERE, "_build")
@@ -44,7 +44,7 @@ def hip_runtime_link_flags():
 
 
 def _newest_input():
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "agc.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "agc.h"), os.path.join(HERE, "..", "include", "agc_debug.h")]
     return max(os.path.getmtime(f) for f in deps)
 
 

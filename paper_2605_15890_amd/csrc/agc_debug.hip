@@ -1,0 +1,85 @@
+// Measurement kernels (include/agc_debug.h): a plain copy of known traffic and the bare access
+// pattern of the two streaming passes.  Not part of the method.
+#include "agc_device.h"
+#include "agc_kernels.h"
+
+namespace agc {
+
+// =======================================================================================
+// counter calibration: a copy that moves exactly `bytes` in and `bytes` out
+// =======================================================================================
+__global__ __launch_bounds__(kWgThreads) void k_calibration_copy(const float4* __restrict__ src,
+                                                                 float4* __restrict__ dst, int64_t n16)
+{
+    const int64_t i = (int64_t)blockIdx.x * kWgThreads + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream)
+{
+    const int64_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)((n16 + kWgThreads - 1) / kWgThreads);
+    hipLaunchKernelGGL(k_calibration_copy, dim3(grid), dim3(kWgThreads), 0, stream,
+                       static_cast<const float4*>(src), static_cast<float4*>(dst), n16);
+    return hipGetLastError();
+}
+
+// =======================================================================================
+// access pattern of the scale pass (reads) and the quantize pass (reads + one small piece per
+// row and wave into the row's own output stream)
+// =======================================================================================
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) f32x4_t* global_f32x4_w;
+
+template <bool WRITE>
+__global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restrict__ G, int64_t ldg, int k,
+                                                            int64_t nblocks, int pieces, f32x4_t* out)
+{
+    constexpr int P = 4;  // rows in flight, as in the passes
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int lane = threadIdx.x % kWave;
+    const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
+    if (block >= nblocks) return;
+    LaneCoords lc;
+    lc.lane4 = lane;
+    lc.byte_off = 16u * (uint32_t)lane;
+    lc.nvalid = 4;
+    lc.wave_ragged = false;
+    const float* row = G + block * (int64_t)kBlockCoords;
+    float4 ring[P];
+#pragma unroll
+    for (int r = 0; r < P; ++r) ring[r] = load_row4<false, true>(row + (int64_t)(r < k ? r : k - 1) * ldg, lc);
+    float acc = 0.f;
+    const int64_t stream_pieces = nblocks * pieces;  // 16-byte pieces per output stream
+    for (int j0 = 0; j0 < k; j0 += P) {
+#pragma unroll
+        for (int r = 0; r < P; ++r) {
+            const int j = j0 + r;
+            if (j >= k) break;
+            const float4 cur = ring[r];
+            if (j + P < k) ring[r] = load_row4<false, true>(row + (int64_t)(j + P) * ldg, lc);
+            acc = fmaxf(acc, fmaxf(fmaxf(cur.x, cur.y), fmaxf(cur.z, cur.w)));
+            if (WRITE && lane < pieces)
+                __builtin_nontemporal_store(f32x4_t{cur.x, cur.y, cur.z, cur.w},
+                                            (global_f32x4_w)(out + (int64_t)j * stream_pieces + block * pieces + lane));
+        }
+    }
+    if (acc == 1.2345678e37f) out[0] = f32x4_t{acc, acc, acc, acc};  // keeps the loads alive; never true for finite data in practice
+}
+
+hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, void* out,
+                              hipStream_t stream)
+{
+    const int64_t nblocks = d / kBlockCoords;
+    if (nblocks == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
+    if (piece_bytes > 0)
+        hipLaunchKernelGGL((k_stream_rows<true>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
+                           piece_bytes / 16, static_cast<f32x4_t*>(out));
+    else
+        hipLaunchKernelGGL((k_stream_rows<false>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks, 0,
+                           static_cast<f32x4_t*>(out));
+    return hipGetLastError();
+}
+
+}  // namespace agc

@@ -137,7 +137,10 @@ hipError_t launch_ls_partial_gradients(const void* X, int64_t n_rows, int n_feat
                                        float* resid, float* partial, hipStream_t stream);
 hipError_t launch_gd_update(float* beta, const float* ghat, float lr, int64_t d, hipStream_t stream);
 
-// plain streaming copy of `bytes` (multiple of 16) bytes, used to calibrate hardware counters
+// measurement kernels (agc_debug.hip): plain streaming copy of `bytes` (multiple of 16) bytes, and
+// the bare row-walk access pattern of the streaming passes (piece_bytes = 0: reads only)
 hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
+hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, void* out,
+                              hipStream_t stream);
 
 }  // namespace agc
