@@ -355,6 +355,7 @@ agc_status encode_quantize_impl(agc_ctx* c, const float* G, int64_t ldg, const u
         qs.bits[i] = bits[i];
         qs.codes[i] = codes[i];
     }
+    agc::stage_starts(qs.bits, c->n, qs.stage_start);
     hipError_t e;
     if (c->opts.bucket) {  // one pass: every block finds its own scale
         KernelTimer t{c, 2, stream};
@@ -389,7 +390,7 @@ agc_status encode_quantize_impl(agc_ctx* c, const float* G, int64_t ldg, const u
     {
         KernelTimer t{c, 2, stream};
         if ((st = t.begin()) != AGC_OK) return st;
-        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, seed, step, ghat, stream);
+        e = agc::launch_quantize(G, ldg, c->n, c->k, c->d, code, c->ws, qs.bits, seed, step, ghat, stream);
         if (e != hipSuccess) return hip_fail(c, e, "quantize launch");
         if ((st = t.end()) != AGC_OK) return st;
     }

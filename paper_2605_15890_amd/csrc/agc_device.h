@@ -247,7 +247,7 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)]
                                           float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                           const float*& next_row, int64_t ldg, int k,
                                           const float* __restrict__ bval, const LaneCoords& lc,
-                                          int j0, Epi& epi)
+                                          int j0, float (&coef)[S], Epi& epi)
 {
     constexpr int P = RingShapeT<S, PF>::P;
     constexpr int R = RingShapeT<S, PF>::R;
@@ -267,11 +267,18 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)]
     if (STEADY || (i >= 0 && i < k)) {
         if (!STEADY && S > 1 && i == 0)
             stash_fill<S, PF, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
-        const float* bv = bval + (int64_t)i * S;
-        float4 f = mul4(bv[0], ring[(r + R - (S - 1)) % R]);
+        // the worker's coefficients were requested one worker earlier (the scalar read is then
+        // over by the time they are used); request the next worker's now
+        float next[S];
+        const float* bv = bval + (int64_t)(i + 1 < k ? i + 1 : i) * S;
 #pragma unroll
-        for (int u = 1; u < S; ++u) f = fma4(bv[u], ring[(r + R - (S - 1) + u) % R], f);
+        for (int u = 0; u < S; ++u) next[u] = bv[u];
+        float4 f = mul4(coef[0], ring[(r + R - (S - 1)) % R]);
+#pragma unroll
+        for (int u = 1; u < S; ++u) f = fma4(coef[u], ring[(r + R - (S - 1) + u) % R], f);
         epi.template worker<(((r + R - (S - 1)) & 1) == 0)>(i, f);
+#pragma unroll
+        for (int u = 0; u < S; ++u) coef[u] = next[u];
     }
 }
 
@@ -280,9 +287,9 @@ __device__ __forceinline__ void ring_round(float4 (&ring)[(RingShapeT<S, PF>::R)
                                            float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                            const float*& next_row, int64_t ldg, int k,
                                            const float* __restrict__ bval, const LaneCoords& lc,
-                                           int j0, Epi& epi, std::integer_sequence<int, Rs...>)
+                                           int j0, float (&coef)[S], Epi& epi, std::integer_sequence<int, Rs...>)
 {
-    (ring_step<S, PF, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, epi), ...);
+    (ring_step<S, PF, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi), ...);
 }
 
 template <int S, int PF, class Epi>
@@ -308,12 +315,15 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
             next_row += (r + 1 < k) ? ldg : 0;
         }
     }
+    float coef[S];  // coefficients of the worker that is formed next
+#pragma unroll
+    for (int u = 0; u < S; ++u) coef[u] = bval[u];
     int j0 = 0;
-    ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+    ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
     for (j0 = R; j0 + R - 1 < k; j0 += R)
-        ring_round<S, PF, true>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, PF, true>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
     for (; j0 < steps; j0 += R)
-        ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, epi, seq);
+        ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -39,8 +39,41 @@ struct WorkerQ {
     // bucket-wise scales w_i / L_i) and whether it arrived
     float coef;
     uint32_t arrived;
-    uint32_t pad[2];
+    // where the worker's codes wait in the workgroup's LDS staging area before they leave as whole
+    // 128-byte lines: first 16-byte piece of the worker (a workgroup stages 8 * bits pieces per
+    // worker: four blocks of 2 * bits), and whether the area is written out after this worker
+    uint32_t stage_piece;
+    uint32_t flush;
 };
+static_assert(sizeof(WorkerQ) == 32, "one record is two 16-byte scalar loads");
+
+// The staging area of a workgroup holds the codes of consecutive workers whose bit-widths sum to
+// at most kStageBits (8 * kStageBits pieces of 16 bytes); workers beyond that start a new fill.
+constexpr int kStageBits = 256;
+
+// Places the workers in the staging area (host side): start[i] = sum of the bit-widths staged
+// before worker i in its fill (< kStageBits, fits a byte); a fill ends before the worker that
+// would overflow it, and that worker starts the next one at 0.
+inline void stage_starts(const uint8_t* bits, int n, uint8_t* start)
+{
+    int acc = 0;
+    for (int j = 0; j < n; ++j) {
+        if (acc + bits[j] > kStageBits) acc = 0;
+        start[j] = (uint8_t)acc;
+        acc += bits[j];
+    }
+}
+// largest fill over all groups, in bits (host side: sizes the LDS area of a launch)
+inline int stage_bits_needed(const uint8_t* bits, int n)
+{
+    int acc = 0, most = 0;
+    for (int j = 0; j < n; ++j) {
+        if (acc + bits[j] > kStageBits) acc = 0;
+        acc += bits[j];
+        if (acc > most) most = acc;
+    }
+    return most;
+}
 
 // one arrived worker as the decode pass sees it
 struct WorkerD {
@@ -66,6 +99,7 @@ constexpr int kMaxSlots = 256;  // rows of the max-abs array; a block folds into
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];
     uint8_t bits[kArgWorkers];
+    uint8_t stage_start[kArgWorkers];  // stage_starts() of the bit-widths
 };
 
 struct StepWeights {       // decode side of a fused step, as kernel arguments of the table kernels
@@ -100,9 +134,10 @@ hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
                                  const Workspace& ws, float* scales, hipStream_t stream);
 // K2: fused encode + stochastic quantize + bit-pack.
 // ghat != nullptr: fused step (the table must have been written with sw.fuse != 0).
+// bits: host array of the n bit-widths (sizes the LDS staging area; the table holds them too).
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
-                           const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           float* ghat, hipStream_t stream);
+                           const CodeDev& code, const Workspace& ws, const uint8_t* bits, uint64_t seed,
+                           uint64_t step, float* ghat, hipStream_t stream);
 // Bucket-wise scales (one per 256-coordinate block and worker): a table prologue, then ONE pass
 // over G that derives each block's scale from the block itself.  scales: n x nb, nb = ceil(d/256).
 hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int64_t d, const CodeDev& code,

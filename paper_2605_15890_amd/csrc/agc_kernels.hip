@@ -269,7 +269,9 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     if (tid == 0) {
         scales[i] = scale;
         const int b = out.bits[i];
-        WorkerQ e{inv16_of(scale, b), (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
+        // the staging area is written out after the last worker and before every worker that starts a new fill
+        const uint32_t flush = (i == n - 1 || out.stage_start[i + 1] == 0) ? 1u : 0u;
+        WorkerQ e{inv16_of(scale, b), (uint32_t)b, out.codes[i], 0.f, 0u, 8u * out.stage_start[i], flush};
         if (sw.fuse) {  // decode weight of one grid unit, as the decode prologue forms it
             const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
             e.coef = (float)(((double)sw.w[i] * (double)scale) / L);
@@ -303,7 +305,8 @@ __global__ __launch_bounds__(kWgThreads) void k_quant_table(int n, QuantStreams 
     // bucket-wise scales: the multiplier is num / scale with the block's own scale; the record
     // carries the numerator L * 2^16 (2^15 for a one-bit worker)
     const float num = b >= 2 ? (float)(((1u << (b - 1)) - 1u) << 16) : 32768.0f;
-    WorkerQ e{num, (uint32_t)b, out.codes[i], 0.f, 0u, {0u, 0u}};
+    const uint32_t flush = (i == n - 1 || out.stage_start[i + 1] == 0) ? 1u : 0u;
+    WorkerQ e{num, (uint32_t)b, out.codes[i], 0.f, 0u, 8u * out.stage_start[i], flush};
     if (sw.fuse) {
         const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
         e.coef = (float)((double)sw.w[i] / L);
@@ -321,17 +324,17 @@ hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat};
+                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat, nullptr, stage_bits_needed(out.bits, n)};
     return scale_mode == 0 ? launch_quantize_band2(G, code, ws, a, stream)
                            : launch_quantize_band1(G, code, ws, a, stream);
 }
 
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
-                           const CodeDev& code, const Workspace& ws, uint64_t seed, uint64_t step,
-                           float* ghat, hipStream_t stream)
+                           const CodeDev& code, const Workspace& ws, const uint8_t* bits, uint64_t seed,
+                           uint64_t step, float* ghat, hipStream_t stream)
 {
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                nullptr, 0, ghat};
+                nullptr, 0, ghat, nullptr, stage_bits_needed(bits, n)};
     return launch_quantize_band0(G, code, ws, a, stream);
 }
 

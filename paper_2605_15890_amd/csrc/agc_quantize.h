@@ -20,11 +20,17 @@ struct QuantArgs {
     int64_t nb;
     float* ghat;    // fused step only
     const WindowRec* win;  // monotone-interval codes only; filled in by the launcher
+    int stage_bits;        // largest sum of bit-widths one fill of the staging area holds (<= kStageBits)
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // one 16-byte piece of a stream
 
-constexpr int kStageWords = 64 * 4 + 4;  // 16 bytes per lane (256 codes of up to 16 bits fill half), plus spill of zero bits
+// LDS staging area of a workgroup, in 16-byte pieces: 8 * bits pieces per worker (the four blocks
+// of the workgroup, 2 * bits pieces each), plus one piece that takes the zero bits the packer
+// spills past a block's last word
+__host__ __device__ constexpr int stage_pieces(int stage_bits) { return 8 * stage_bits + 1; }
+
 // raw buffer descriptor, last word: 32-bit untyped data format of this target; the bounds check is
 // on the byte offset against num_records (stride 0)
 constexpr int kBufferRsrcFlags = 0x00020000;
@@ -62,14 +68,6 @@ __device__ __forceinline__ float grid_pos(float f, float inv)
     return fabsf(f) * inv;
 }
 
-__device__ __forceinline__ void wave_lds_fence()
-{
-    // LDS operations of one wave execute in issue order; this only pins the compiler's order
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // BUCKET 0: the worker's multiplier comes from the table (one scale per vector).
 // BUCKET 1 / 2: one scale per 256-coordinate block, derived here from the block itself (largest
 // magnitude / Euclidean norm), stored by lane 0, and turned into the multiplier with one binary32
@@ -77,24 +75,79 @@ __device__ __forceinline__ void wave_lds_fence()
 // FUSE: the pass also accumulates the master's estimate (Sec. II-A aggregation) from the codes it
 // has just formed: arrived workers in ascending order, one fused multiply-add each from 0, the
 // arithmetic of the stand-alone decode kernel, so both give the same bits.
+// Payload path: a worker's codes are not stored when they are formed.  Every wave ORs its block's
+// 8b words into the workgroup's LDS staging area (worker-major, then block, so that the four
+// blocks of a worker lie in stream order); when the area is full, or after the last worker, the
+// workgroup meets at a barrier and writes each worker's 128*b bytes as one contiguous, line-aligned
+// piece of its stream.  Stores of 64..96 bytes per wave and worker, as a wave alone would issue
+// them, reach memory as partial lines and cost several times their bytes on this memory system.
 template <int BUCKET, bool FUSE>
 struct EpiQuant {
-    static constexpr bool kStoresPerWorker = true;  // the payload leaves inside the worker loop
+    static constexpr bool kStoresPerWorker = true;  // stores may happen inside the worker loop (staging flush)
     static constexpr int kPrefetchRows = AGC_PREFETCH_ROWS;
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
-    uint32_t* stage;     // this wave's LDS staging words, all zero between workers
+    uint32_t* stage;     // the workgroup's LDS staging area, all zero between fills
     int lane;
-    uint32_t lane_byte16;  // 16 * lane
+    int wave;            // this wave's block inside the workgroup (0..3)
+    int n;               // workers
+    int64_t wg;          // index of the workgroup = index of its group of four blocks
+    int wg_groups;       // 128-code groups of the workgroup's four blocks that exist in the streams (1..8)
     int64_t block;       // index of this wave's 256-coordinate block
-    int groups_valid;    // 128-code groups of this block that exist in the streams (1 or 2)
     uint32_t ctr0;       // m >> 2 of this lane's coordinates
     int nvalid;
     bool wave_ragged;    // wave-uniform: some lane has coordinates >= d
     uint32_t keep2, keep3;  // second half of the Philox block, for the odd worker of the pair
     float* scales;          // bucket-wise scales: n x nb
     int64_t nb;
+    int group_first;        // first worker of the fill that is being staged
     float acc[4];           // fused step: this lane's four coordinates of the estimate
+    WorkerQ pend;           // record of the worker that comes next, requested one worker early
+
+    // The workgroup writes out the fill that ends with worker `last`.  Every wave of the
+    // workgroup calls this for the same workers in the same order (also a wave whose block lies
+    // past the end of the vector), so the barriers match.  The waves share the workers of the
+    // fill; a worker's 8b pieces leave as one store of 128*b contiguous bytes through a buffer
+    // descriptor that covers exactly the bytes of the stream that exist, so the hardware's range
+    // check drops the pieces past the end of the vector.  Pieces are handed back zeroed.
+    __device__ __forceinline__ void flush_fill(int last)
+    {
+        __syncthreads();
+        u32x4_t* pieces = reinterpret_cast<u32x4_t*>(stage);
+        for (int j = group_first + wave; j <= last; j += kWavesPerWg) {
+            const WorkerQ w = load_uniform(wq + j);
+            const int b = (int)w.bits;
+            const int np = 8 * b;  // pieces of this worker in the area
+            const uint64_t dst_bits = (uint64_t)w.codes + (uint64_t)wg * (uint64_t)(128 * b);
+            const uint32_t dst_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dst_bits);
+            const uint32_t dst_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dst_bits >> 32));
+            char* dst = (char*)(((uint64_t)dst_hi << 32) | (uint64_t)dst_lo);
+            const int valid_bytes = __builtin_amdgcn_readfirstlane(16 * b * wg_groups);
+            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, valid_bytes, kBufferRsrcFlags);
+            for (int off = 0; off < np; off += kWave) {
+                const int piece = off + lane;
+                u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
+                if (piece < np) {
+                    u32x4_t* sp = pieces + (w.stage_piece + (uint32_t)piece);
+                    v = *sp;
+                    *sp = u32x4_t{0u, 0u, 0u, 0u};
+                }
+                // lanes with piece >= np lie at or past 128*b >= valid_bytes: dropped by the range check
+                __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, 16 * piece, 0, kBufferNonTemporal);
+            }
+        }
+        group_first = last + 1;
+        if (last + 1 < n) __syncthreads();  // the area is reused by the next fill
+    }
+
+    // a wave without a block (past the end of the vector) still takes part in every flush
+    __device__ __forceinline__ void flush_only()
+    {
+        for (int i = 0; i < n; ++i) {
+            const WorkerQ w = load_uniform(wq + i);
+            if (w.flush) flush_fill(i);
+        }
+    }
 
     __device__ __forceinline__ float block_multiplier(int i, const float4& f, float num, float& scale)
     {
@@ -188,7 +241,10 @@ struct EpiQuant {
 
     __device__ __forceinline__ void finish(int i, const float4& f, uint32_t wa, uint32_t wb)
     {
-        const WorkerQ q = load_uniform(wq + i);  // wave-uniform scalar read
+        // wave-uniform scalar reads; workers come in ascending order, so the record of this one
+        // was requested while the previous one was quantized
+        const WorkerQ q = pend;
+        pend = load_uniform(wq + (i + 1 < n ? i + 1 : i));
         const int b = (int)q.bits;
         uint32_t c[4], lev[4];
         float scale = 0.f;
@@ -214,9 +270,10 @@ struct EpiQuant {
             }
         }
 
-        // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits
+        // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits, the block's
+        // 8b words start at piece q.stage_piece + wave*2b of the staging area
         const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
-        uint32_t* slot = stage + (bitpos >> 5);
+        uint32_t* slot = stage + 4u * (q.stage_piece + (uint32_t)wave * 2u * (uint32_t)b) + (bitpos >> 5);
         const uint32_t sh = bitpos & 31u;
         if (b <= 8) {
             const uint32_t chunk = c[0] | (c[1] << b) | (c[2] << (2 * b)) | (c[3] << (3 * b));
@@ -232,32 +289,7 @@ struct EpiQuant {
             atomicOr(slot + 1, (uint32_t)(v >> 32));
             atomicOr(slot + 2, top);
         }
-        wave_lds_fence();
-        // the block's 8b words leave as one contiguous, coalesced store; the staging words
-        // are handed back zeroed
-        // (16 bytes per lane: 2b lanes cover the 8b words; the payload is not read again, so the
-        // store is non-temporal)
-        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-        // Read-out and store run for all 64 lanes without a branch: every lane hands its 16 staged
-        // bytes over (lanes past the block's 2b pieces hold zeros and hand zeros back), and the
-        // store goes through a buffer descriptor that covers exactly this block's bytes of the
-        // stream, so the hardware's range check drops the lanes beyond it.  Behind a branch that
-        // may skip the store the compiler cannot count outstanding memory operations, and every
-        // wait for a row of G then also waits for the most recent stores.
-        u32x4_t* sp = reinterpret_cast<u32x4_t*>(stage) + lane;
-        const u32x4_t v = *sp;
-        *sp = u32x4_t{0u, 0u, 0u, 0u};
-        const uint32_t piece_bytes = 16u * (uint32_t)b;                      // 128 codes
-        // the block's first byte in the stream is wave-uniform: say so, so that the descriptor
-        // lives in scalar registers on every path
-        const uint64_t dst_bits = (uint64_t)q.codes + (uint64_t)block * (2u * piece_bytes);
-        const uint32_t dst_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dst_bits);  // the builtin returns int:
-        const uint32_t dst_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dst_bits >> 32));  // widen as unsigned
-        char* blk_dst = (char*)(((uint64_t)dst_hi << 32) | (uint64_t)dst_lo);
-        const int blk_bytes = __builtin_amdgcn_readfirstlane((int)(piece_bytes * (uint32_t)groups_valid));
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(blk_dst, 0, blk_bytes, kBufferRsrcFlags);
-        __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)lane_byte16, 0, kBufferNonTemporal);
-        wave_lds_fence();
+        if (q.flush) flush_fill(i);  // wave-uniform, and the same for every wave of the workgroup
     }
 };
 
@@ -272,39 +304,35 @@ __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(S ==
                                                          const float* __restrict__ val,
                                                          const WorkerQ* __restrict__ wq, QuantArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t lds_stage[kWavesPerWg][kStageWords];
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds_stage[];  // stage_pieces(a.stage_bits) pieces
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
     const int lane = threadIdx.x % kWave;
-#ifdef AGC_XCD_ORDER
-    int64_t wg = blockIdx.x;
-    {
-        const int64_t per = gridDim.x / 8;
-        if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
-    }
+    const int64_t wg = blockIdx.x;
     const int64_t block = wg * kWavesPerWg + wave;
-#else
-    const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
-#endif
     const int64_t base = block * (int64_t)kBlockCoords;
-    for (int w = lane; w < kStageWords; w += kWave) lds_stage[wave][w] = 0u;
-    wave_lds_fence();
-    if (base >= a.d) return;
-    const LaneCoords lc = lane_coords(base, lane, a.d);
-    const int64_t groups_left = (a.d + 127) / 128 - 2 * block;
-    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage[wave], lane, 16u * (uint32_t)lane, block,
-                               groups_left >= 2 ? 2 : 1, (uint32_t)((base + 4 * lane) >> 2), lc.nvalid,
-                               lc.wave_ragged, 0u, 0u, a.scales, a.nb, {0.f, 0.f, 0.f, 0.f}};
+    {
+        u32x4_t* pieces = reinterpret_cast<u32x4_t*>(lds_stage);
+        const int np = stage_pieces(a.stage_bits);
+        for (int p = threadIdx.x; p < np; p += kWgThreads) pieces[p] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();
+    const int64_t groups_left = (a.d + 127) / 128 - 8 * wg;  // >= 1: the workgroup's first block exists
+    const bool has_block = base < a.d;
+    LaneCoords lc{};
+    if (has_block) lc = lane_coords(base, lane, a.d);
+    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage, lane, wave, a.n, wg,
+                               groups_left >= 8 ? 8 : (int)groups_left, block, (uint32_t)((base + 4 * lane) >> 2),
+                               lc.nvalid, lc.wave_ragged, 0u, 0u, a.scales, a.nb, 0, {0.f, 0.f, 0.f, 0.f},
+                               load_uniform(wq)};
+    if (!has_block) {  // nothing to encode, but the other waves of the workgroup wait at the flushes
+        epi.flush_only();
+        return;
+    }
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
         if (lc.nvalid == 4) {
-#ifdef AGC_GHAT_NT
-            typedef float f32x4_t __attribute__((ext_vector_type(4)));
-            __builtin_nontemporal_store(f32x4_t{epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]},
-                                        (__attribute__((address_space(1))) f32x4_t*)dst);
-#else
             *reinterpret_cast<float4*>(dst) = make_float4(epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]);
-#endif
         } else {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
@@ -322,12 +350,14 @@ static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const W
     if (S < 0 && !a.win) return hipErrorInvalidValue;  // the window driver reads the records
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
+    if (a.stage_bits < 1 || a.stage_bits > kStageBits) return hipErrorInvalidValue;
+    const unsigned lds_bytes = 16u * (unsigned)stage_pieces(a.stage_bits);
     if (a.ghat)
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
-                           code.col, code.val, ws.wq, a);
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), lds_bytes, stream, G,
+                           code.row_ptr, code.col, code.val, ws.wq, a);
     else
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), 0, stream, G, code.row_ptr,
-                           code.col, code.val, ws.wq, a);
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), lds_bytes, stream, G,
+                           code.row_ptr, code.col, code.val, ws.wq, a);
     return hipGetLastError();
 }
 
