@@ -275,12 +275,15 @@ def measured_ceilings(api, G, k, d, scratch):
     out["pattern_read_ms"] = round(ms, 4)
     out["pattern_read_GBps"] = round(g_bytes / (ms * 1e-3) / 1e9, 1)
     piece = 96
-    ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch))
     w_bytes = float(k) * (d // 256) * piece
+    ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=False))
+    out["pattern_read_write_per_wave_ms"] = round(ms, 4)
+    ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=True))
     out["pattern_read_write_ms"] = round(ms, 4)
     out["pattern_read_write_GBps"] = round((g_bytes + w_bytes) / (ms * 1e-3) / 1e9, 1)
     out["pattern_note"] = (f"bare row walk over G ({g_bytes / 1e9:.2f} GB); with writes: plus {w_bytes / 1e9:.3f} GB "
-                           f"in {piece}-byte pieces to {k} streams")
+                           f"in {piece}-byte pieces per block to {k} streams, stored per wave after every row "
+                           f"(per_wave) or per workgroup as {4 * piece}-byte lines after a barrier (the quantize pass's form)")
     return out
 
 

@@ -43,16 +43,21 @@ agc_status agc_calibration_copy(void *dst_dev, const void *src_dev, int64_t byte
  * arithmetic worth the name: one wave per 256 consecutive coordinates walks over the k rows of G
  * (16 bytes per lane and row, non-temporal, four rows in flight) exactly as the register-ring
  * driver does.  piece_bytes == 0: reads only (the scale pass).  piece_bytes > 0 (a multiple of 16,
- * at most 1024): after every row the wave also writes piece_bytes bytes, non-temporal, to that
- * row's own output stream, the way the quantize pass writes a b-bit worker's 32*b bytes per
- * block; out_dev then holds k streams of floor(d/256) * piece_bytes bytes each, back to back.
+ * at most 1024): the kernel also writes piece_bytes bytes per block and row, non-temporal, to that
+ * row's own output stream, the way the quantize pass writes a b-bit worker's 32*b bytes per block;
+ * out_dev then holds k streams of floor(d/256) * piece_bytes bytes each, back to back.
+ *   wg_flush == 0: every wave stores its piece right after the row (what a wave on its own would do:
+ *                  64..96-byte stores that reach memory as partial lines);
+ *   wg_flush != 0: a workgroup (four blocks) keeps its pieces until it has walked all rows and then,
+ *                  after one barrier, writes 4 * piece_bytes contiguous bytes per row (what the
+ *                  quantize pass does through its LDS staging area).
  * Only whole blocks are touched (floor(d/256) of them).  What this kernel reaches is what the
  * memory system delivers for that traffic, whatever the arithmetic on top of it.
  *   G_dev    device, k x d binary32, row stride ldg (multiple of 4), 16-byte aligned; read-only
  *   out_dev  device, 16-byte aligned, at least max(16, k * floor(d/256) * piece_bytes) bytes
  */
 agc_status agc_debug_stream_rows(const float *G_dev, int64_t ldg, int k, int64_t d, int piece_bytes,
-                                 void *out_dev, void *hip_stream);
+                                 int wg_flush, void *out_dev, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -31,7 +31,10 @@ hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hi
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) f32x4_t* global_f32x4_w;
 
-template <bool WRITE>
+// WRITE 0: reads only.  1: every wave writes `pieces` 16-byte pieces to the row's stream right after
+// the row.  2: nothing is written until the workgroup has walked all rows; then, after one barrier,
+// its four blocks' pieces of every row leave as 4 * pieces contiguous pieces (whole, aligned lines).
+template <int WRITE>
 __global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restrict__ G, int64_t ldg, int k,
                                                             int64_t nblocks, int pieces, f32x4_t* out)
 {
@@ -39,46 +42,64 @@ __global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restr
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int64_t block = (int64_t)blockIdx.x * kWavesPerWg + wave;
-    if (block >= nblocks) return;
-    LaneCoords lc;
-    lc.lane4 = lane;
-    lc.byte_off = 16u * (uint32_t)lane;
-    lc.nvalid = 4;
-    lc.wave_ragged = false;
-    const float* row = G + block * (int64_t)kBlockCoords;
-    float4 ring[P];
-#pragma unroll
-    for (int r = 0; r < P; ++r) ring[r] = load_row4<false, true>(row + (int64_t)(r < k ? r : k - 1) * ldg, lc);
-    float acc = 0.f;
     const int64_t stream_pieces = nblocks * pieces;  // 16-byte pieces per output stream
-    for (int j0 = 0; j0 < k; j0 += P) {
+    float acc = 0.f;
+    float4 last = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (block < nblocks) {
+        LaneCoords lc;
+        lc.lane4 = lane;
+        lc.byte_off = 16u * (uint32_t)lane;
+        lc.nvalid = 4;
+        lc.wave_ragged = false;
+        const float* row = G + block * (int64_t)kBlockCoords;
+        float4 ring[P];
 #pragma unroll
-        for (int r = 0; r < P; ++r) {
-            const int j = j0 + r;
-            if (j >= k) break;
-            const float4 cur = ring[r];
-            if (j + P < k) ring[r] = load_row4<false, true>(row + (int64_t)(j + P) * ldg, lc);
-            acc = fmaxf(acc, fmaxf(fmaxf(cur.x, cur.y), fmaxf(cur.z, cur.w)));
-            if (WRITE && lane < pieces)
-                __builtin_nontemporal_store(f32x4_t{cur.x, cur.y, cur.z, cur.w},
-                                            (global_f32x4_w)(out + (int64_t)j * stream_pieces + block * pieces + lane));
+        for (int r = 0; r < P; ++r) ring[r] = load_row4<false, true>(row + (int64_t)(r < k ? r : k - 1) * ldg, lc);
+        for (int j0 = 0; j0 < k; j0 += P) {
+#pragma unroll
+            for (int r = 0; r < P; ++r) {
+                const int j = j0 + r;
+                if (j >= k) break;
+                const float4 cur = ring[r];
+                if (j + P < k) ring[r] = load_row4<false, true>(row + (int64_t)(j + P) * ldg, lc);
+                acc = fmaxf(acc, fmaxf(fmaxf(cur.x, cur.y), fmaxf(cur.z, cur.w)));
+                last = cur;
+                if (WRITE == 1 && lane < pieces)
+                    __builtin_nontemporal_store(f32x4_t{cur.x, cur.y, cur.z, cur.w},
+                                                (global_f32x4_w)(out + (int64_t)j * stream_pieces + block * pieces + lane));
+            }
+        }
+    }
+    if (WRITE == 2) {
+        __syncthreads();
+        const int64_t first = (int64_t)blockIdx.x * kWavesPerWg;           // first block of the workgroup
+        const int64_t left = nblocks - first;
+        const int per_row = pieces * (int)(left < kWavesPerWg ? left : kWavesPerWg);
+        const int total = k * per_row;
+        for (int q = threadIdx.x; q < total; q += kWgThreads) {
+            const int j = q / per_row, r = q - j * per_row;
+            __builtin_nontemporal_store(f32x4_t{last.x, last.y, last.z, last.w},
+                                        (global_f32x4_w)(out + (int64_t)j * stream_pieces + first * pieces + r));
         }
     }
     if (acc == 1.2345678e37f) out[0] = f32x4_t{acc, acc, acc, acc};  // keeps the loads alive; never true for finite data in practice
 }
 
-hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, void* out,
+hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, int wg_flush, void* out,
                               hipStream_t stream)
 {
     const int64_t nblocks = d / kBlockCoords;
     if (nblocks == 0) return hipSuccess;
     const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
-    if (piece_bytes > 0)
-        hipLaunchKernelGGL((k_stream_rows<true>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
-                           piece_bytes / 16, static_cast<f32x4_t*>(out));
+    f32x4_t* o = static_cast<f32x4_t*>(out);
+    if (piece_bytes == 0)
+        hipLaunchKernelGGL((k_stream_rows<0>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks, 0, o);
+    else if (!wg_flush)
+        hipLaunchKernelGGL((k_stream_rows<1>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
+                           piece_bytes / 16, o);
     else
-        hipLaunchKernelGGL((k_stream_rows<false>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks, 0,
-                           static_cast<f32x4_t*>(out));
+        hipLaunchKernelGGL((k_stream_rows<2>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
+                           piece_bytes / 16, o);
     return hipGetLastError();
 }
 

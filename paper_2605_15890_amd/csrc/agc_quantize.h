@@ -26,10 +26,19 @@ struct QuantArgs {
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // one 16-byte piece of a stream
 
-// LDS staging area of a workgroup, in 16-byte pieces: 8 * bits pieces per worker (the four blocks
-// of the workgroup, 2 * bits pieces each), plus one piece that takes the zero bits the packer
-// spills past a block's last word
-__host__ __device__ constexpr int stage_pieces(int stage_bits) { return 8 * stage_bits + 1; }
+// Waves (= 256-coordinate blocks) per workgroup of the quantize pass.  A worker's codes leave in
+// pieces of 32 * kQuantWaves * b contiguous bytes; the staging area grows by the same factor.
+#ifndef AGC_K2_WG_WAVES
+#define AGC_K2_WG_WAVES 4
+#endif
+constexpr int kQuantWaves = AGC_K2_WG_WAVES;
+constexpr int kQuantThreads = kWave * kQuantWaves;
+static_assert(kQuantWaves % 4 == 0 && kQuantWaves <= 16, "the per-worker table counts pieces for four waves");
+
+// LDS staging area of a workgroup, in 16-byte pieces: 2 * kQuantWaves * bits pieces per worker
+// (the blocks of the workgroup, 2 * bits pieces each), plus one piece that takes the zero bits the
+// packer spills past a block's last word
+__host__ __device__ constexpr int stage_pieces(int stage_bits) { return 2 * kQuantWaves * stage_bits + 1; }
 
 // raw buffer descriptor, last word: 32-bit untyped data format of this target; the bounds check is
 // on the byte offset against num_records (stride 0)
@@ -88,11 +97,12 @@ struct EpiQuant {
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
     uint32_t* stage;     // the workgroup's LDS staging area, all zero between fills
+    float* stage_scales; // bucket-wise scales: [n][kQuantWaves] floats behind the staging area
     int lane;
-    int wave;            // this wave's block inside the workgroup (0..3)
+    int wave;            // this wave's block inside the workgroup
     int n;               // workers
     int64_t wg;          // index of the workgroup = index of its group of four blocks
-    int wg_groups;       // 128-code groups of the workgroup's four blocks that exist in the streams (1..8)
+    int wg_groups;       // 128-code groups of the workgroup's blocks that exist in the streams (1..2*kQuantWaves)
     int64_t block;       // index of this wave's 256-coordinate block
     uint32_t ctr0;       // m >> 2 of this lane's coordinates
     int nvalid;
@@ -114,30 +124,56 @@ struct EpiQuant {
     {
         __syncthreads();
         u32x4_t* pieces = reinterpret_cast<u32x4_t*>(stage);
-        for (int j = group_first + wave; j <= last; j += kWavesPerWg) {
+        for (int j = group_first + wave; j <= last; j += kQuantWaves) {
             const WorkerQ w = load_uniform(wq + j);
             const int b = (int)w.bits;
-            const int np = 8 * b;  // pieces of this worker in the area
-            const uint64_t dst_bits = (uint64_t)w.codes + (uint64_t)wg * (uint64_t)(128 * b);
+            const int np = 2 * kQuantWaves * b;  // pieces of this worker in the area
+            const uint64_t dst_bits = (uint64_t)w.codes + (uint64_t)wg * (uint64_t)(32 * kQuantWaves * b);
             const uint32_t dst_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dst_bits);
             const uint32_t dst_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dst_bits >> 32));
             char* dst = (char*)(((uint64_t)dst_hi << 32) | (uint64_t)dst_lo);
             const int valid_bytes = __builtin_amdgcn_readfirstlane(16 * b * wg_groups);
             const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, valid_bytes, kBufferRsrcFlags);
+            const uint32_t first = w.stage_piece * (uint32_t)(kQuantWaves / 4);  // the table counts for four waves
             for (int off = 0; off < np; off += kWave) {
                 const int piece = off + lane;
                 u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
                 if (piece < np) {
-                    u32x4_t* sp = pieces + (w.stage_piece + (uint32_t)piece);
+                    u32x4_t* sp = pieces + (first + (uint32_t)piece);
                     v = *sp;
                     *sp = u32x4_t{0u, 0u, 0u, 0u};
                 }
-                // lanes with piece >= np lie at or past 128*b >= valid_bytes: dropped by the range check
+                // lanes with piece >= np lie at or past the worker's bytes >= valid_bytes: dropped by the range check
+#ifndef AGC_ABLATE_STORES
                 __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, 16 * piece, 0, kBufferNonTemporal);
+#endif
             }
         }
         group_first = last + 1;
-        if (last + 1 < n) __syncthreads();  // the area is reused by the next fill
+        if (last + 1 < n) {
+            __syncthreads();  // the area is reused by the next fill
+        } else if (BUCKET != 0) {
+            // after the last worker: the scales of all workers for the workgroup's blocks, one run of
+            // kQuantWaves floats per worker (the barrier above made every wave's entries visible)
+            const int64_t first_block = wg * kQuantWaves;
+            const int have = nb - first_block >= kQuantWaves ? kQuantWaves : (int)(nb - first_block);
+            for (int t = wave * kWave + lane; t < n; t += kQuantThreads) {
+                __attribute__((address_space(1))) float* dst =
+                    (__attribute__((address_space(1))) float*)scales + ((int64_t)t * nb + first_block);
+                if (have == kQuantWaves) {  // one run per worker, dword-aligned (a row of scales starts anywhere)
+                    typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+#pragma unroll
+                    for (int u = 0; u < kQuantWaves; u += 4)
+                        *(__attribute__((address_space(1))) f32x4_a4*)(dst + u) =
+                            f32x4_a4{stage_scales[t * kQuantWaves + u], stage_scales[t * kQuantWaves + u + 1],
+                                     stage_scales[t * kQuantWaves + u + 2], stage_scales[t * kQuantWaves + u + 3]};
+                } else {
+#pragma unroll
+                    for (int u = 0; u < kQuantWaves; ++u)
+                        if (u < have) dst[u] = stage_scales[t * kQuantWaves + u];
+                }
+            }
+        }
     }
 
     // a wave without a block (past the end of the vector) still takes part in every flush
@@ -160,7 +196,9 @@ struct EpiQuant {
             const double s23 = x2 * x2 + x3 * x3;
             scale = (float)sqrt(wave_butterfly_add(s01 + s23));
         }
-        if (lane == 0) *((__attribute__((address_space(1))) float*)scales + ((int64_t)i * nb + block)) = scale;
+        // the block's scale waits in LDS next to the codes ([worker][block of the workgroup]) and
+        // leaves with the last flush: 4-byte stores scattered over n rows cost far more than their bytes
+        if (lane == 0) stage_scales[i * kQuantWaves + wave] = scale;
         // num = L * 2^16 (2^15 for a one-bit worker) comes with the worker's record
         const float q = num / scale;  // correctly rounded binary32 division
         return q <= 3.402823466e+38f ? q : 0.0f;  // scale == 0 gives +inf and ends here too
@@ -273,8 +311,13 @@ struct EpiQuant {
         // bit-pack: this lane's four codes start at bit lane*4b of the block's 256*b bits, the block's
         // 8b words start at piece q.stage_piece + wave*2b of the staging area
         const uint32_t bitpos = __umul24((uint32_t)lane, 4u * (uint32_t)b);
-        uint32_t* slot = stage + 4u * (q.stage_piece + (uint32_t)wave * 2u * (uint32_t)b) + (bitpos >> 5);
+        uint32_t* slot = stage + 4u * (q.stage_piece * (uint32_t)(kQuantWaves / 4) + (uint32_t)wave * 2u * (uint32_t)b) +
+                         (bitpos >> 5);
         const uint32_t sh = bitpos & 31u;
+#ifdef AGC_ABLATE_PACK
+        if (c[0] + c[1] + c[2] + c[3] + sh == 0xFFFFFFF0u) atomicOr(slot, 1u);
+        else
+#endif
         if (b <= 8) {
             const uint32_t chunk = c[0] | (c[1] << b) | (c[2] << (2 * b)) | (c[3] << (3 * b));
             const uint64_t v = (uint64_t)chunk << sh;
@@ -298,30 +341,43 @@ template <int S, int BUCKET, bool FUSE>
 // five-wave limit it otherwise schedules for five and gives up instruction-level parallelism;
 // measured 1.45 ms against 1.51 ms on the metric workload (three: 1.51 ms).  The gather driver
 // (S == 0) lives on occupancy instead and keeps the default.
-__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(S == 0 ? 1 : 4, S == 0 ? 8 : 4))) void k_quantize(const float* __restrict__ G,
+#ifndef AGC_K2_WAVES
+#define AGC_K2_WAVES 4
+#endif
+__global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S == 0 ? 1 : AGC_K2_WAVES, S == 0 ? 8 : AGC_K2_WAVES))) void k_quantize(const float* __restrict__ G,
                                                          const int* __restrict__ row_ptr,
                                                          const int* __restrict__ col,
                                                          const float* __restrict__ val,
                                                          const WorkerQ* __restrict__ wq, QuantArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) uint32_t lds_stage[];  // stage_pieces(a.stage_bits) pieces
+    // stage_pieces(a.stage_bits) pieces, then (bucket-wise scales) n * kQuantWaves floats
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds_stage[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
     const int lane = threadIdx.x % kWave;
+#ifdef AGC_XCD_ORDER
+    int64_t wg = blockIdx.x;
+    {
+        const int64_t per = gridDim.x / 8;
+        if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
+    }
+#else
     const int64_t wg = blockIdx.x;
-    const int64_t block = wg * kWavesPerWg + wave;
+#endif
+    const int64_t block = wg * kQuantWaves + wave;
     const int64_t base = block * (int64_t)kBlockCoords;
     {
         u32x4_t* pieces = reinterpret_cast<u32x4_t*>(lds_stage);
         const int np = stage_pieces(a.stage_bits);
-        for (int p = threadIdx.x; p < np; p += kWgThreads) pieces[p] = u32x4_t{0u, 0u, 0u, 0u};
+        for (int p = threadIdx.x; p < np; p += kQuantThreads) pieces[p] = u32x4_t{0u, 0u, 0u, 0u};
     }
     __syncthreads();
-    const int64_t groups_left = (a.d + 127) / 128 - 8 * wg;  // >= 1: the workgroup's first block exists
+    const int64_t groups_left = (a.d + 127) / 128 - 2 * kQuantWaves * wg;  // >= 1: the workgroup's first block exists
     const bool has_block = base < a.d;
     LaneCoords lc{};
     if (has_block) lc = lane_coords(base, lane, a.d);
-    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage, lane, wave, a.n, wg,
-                               groups_left >= 8 ? 8 : (int)groups_left, block, (uint32_t)((base + 4 * lane) >> 2),
+    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage,
+                               reinterpret_cast<float*>(lds_stage + 4 * stage_pieces(a.stage_bits)), lane, wave, a.n, wg,
+                               groups_left >= 2 * kQuantWaves ? 2 * kQuantWaves : (int)groups_left, block, (uint32_t)((base + 4 * lane) >> 2),
                                lc.nvalid, lc.wave_ragged, 0u, 0u, a.scales, a.nb, 0, {0.f, 0.f, 0.f, 0.f},
                                load_uniform(wq)};
     if (!has_block) {  // nothing to encode, but the other waves of the workgroup wait at the flushes
@@ -349,14 +405,15 @@ static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const W
     a.win = code.win;
     if (S < 0 && !a.win) return hipErrorInvalidValue;  // the window driver reads the records
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
-    const unsigned grid = (unsigned)((nblocks + kWavesPerWg - 1) / kWavesPerWg);
+    const unsigned grid = (unsigned)((nblocks + kQuantWaves - 1) / kQuantWaves);
     if (a.stage_bits < 1 || a.stage_bits > kStageBits) return hipErrorInvalidValue;
-    const unsigned lds_bytes = 16u * (unsigned)stage_pieces(a.stage_bits);
+    const unsigned lds_bytes = 16u * (unsigned)stage_pieces(a.stage_bits) +
+                               (BUCKET != 0 ? (unsigned)(sizeof(float) * kQuantWaves * a.n) : 0u);
     if (a.ghat)
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kWgThreads), lds_bytes, stream, G,
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kQuantThreads), lds_bytes, stream, G,
                            code.row_ptr, code.col, code.val, ws.wq, a);
     else
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kWgThreads), lds_bytes, stream, G,
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kQuantThreads), lds_bytes, stream, G,
                            code.row_ptr, code.col, code.val, ws.wq, a);
     return hipGetLastError();
 }
