@@ -5,6 +5,7 @@ cpu_baseline leg of bench.py.  It never imports the product package.
 All arrays are host numpy arrays.
 """
 import ctypes as C
+import os
 import numpy as np
 
 from . import build as _build
@@ -20,7 +21,8 @@ _f32p = C.POINTER(C.c_float)
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(_build.build())
+        # AGC_ORACLE_LIB: another build of the same source (the sanitizer leg of the tests)
+        _lib = C.CDLL(os.environ.get("AGC_ORACLE_LIB") or _build.build())
         L = _lib
         L.agc_oracle_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
         L.agc_oracle_philox4x32_10.restype = None

@@ -74,6 +74,21 @@ def build(verbose: bool = True, extra=(), incremental: bool = False) -> str:
     return LIB
 
 
+HOST_SAN_LIB = os.path.join(OBJ_DIR, "libagc_host_san.so")
+
+
+def build_host_sanitized() -> str:
+    """The host-only design routines (csrc/agc_host.cpp: bit allocation, code construction) as a
+    library of their own, compiled with plain g++ under AddressSanitizer and
+    UndefinedBehaviorSanitizer.  CPU only; no HIP code is involved."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-Wall",
+           os.path.join(CSRC, "agc_host.cpp"), "-o", HOST_SAN_LIB]
+    subprocess.run(cmd, check=True)
+    return HOST_SAN_LIB
+
+
 if __name__ == "__main__":
     args = sys.argv[1:]
     inc = "--incremental" in args
