@@ -100,8 +100,11 @@ void agc_destroy(agc_ctx *ctx);
  * order of the stored entries inside a row IS the summation order of the encode.  When
  * n == k and every row i stores exactly s <= 8 entries with columns (i+u) mod k, u=0..s-1 in
  * that order (cyclic replication), the kernels take a register sliding-window path that
- * reads every element of G once per pass; any other B takes the generic gather path.  Both
- * give identical bits. */
+ * reads every element of G once per pass; when every row is a run of at most 8 consecutive
+ * ascending columns whose two ends never decrease from one worker to the next (the shape
+ * agc_build_code produces), they take the same kind of path without the wrap-around; any other B
+ * takes the generic gather path, which re-reads shared rows through the caches.  All three give
+ * identical bits (agc_code_path tells which one a context runs). */
 agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col, const float *val);
 
 /* 0 = generic gather path; 1..8 = cyclic-band path with replication s; 102, 104, 108 = monotone-
@@ -147,7 +150,10 @@ const char *agc_last_error(const agc_ctx *ctx);
  * sequential sum starts from 0.0).
  *
  *   G_dev      device, k x d binary32, row-major with row stride ldg elements (ldg >= d,
- *              ldg % 4 == 0, base 16-byte aligned); read-only
+ *              ldg % 4 == 0, base 16-byte aligned); read-only.  The kernels load whole 16-byte
+ *              groups of four coordinates: the allocation must hold (k-1)*ldg + 4*ceil(d/4)
+ *              floats (always true when every row owns its full stride of ldg floats); the up to
+ *              three floats past d in a row are read and ignored
  *   bits_host  host, n bytes
  *   codes_dev  host array of n device pointers; stream i has agc_code_bytes(d, b_i) bytes,
  *              16-byte aligned; fully overwritten, padding included

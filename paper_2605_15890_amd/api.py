@@ -330,6 +330,11 @@ class Context:
     def _check_gradients(self, G):
         if G.dim() != 2 or G.shape[0] < self.k or G.shape[1] < self.d or G.stride(1) != 1:
             raise AgcError(AGC_ESHAPE, f"G must be a ({self.k}, {self.d}) row-major view, got {tuple(G.shape)}")
+        # the kernels read whole groups of four coordinates: the storage behind the view must reach
+        # to the end of the last row's last group
+        need = G.storage_offset() + (self.k - 1) * G.stride(0) + (self.d + 3) // 4 * 4
+        if G.untyped_storage().nbytes() // G.element_size() < need:
+            raise AgcError(AGC_ESHAPE, "the storage behind G ends before the last row's last 16-byte group")
 
     def agc_encode_quantize(self, G, bits, seed, step, codes, scales, stream=None, check=True):
         bits = _np(bits, np.uint8)

@@ -84,7 +84,7 @@ struct WorkerD {
 
 struct Workspace {
     uint32_t* part_max;   // [kMaxSlots][n] running max |f_i| as bit patterns, all zero between steps (max-abs scale)
-    double* part_sq;      // [n][nseg]   per-segment sum of squares             (Euclidean scale)
+    double* part_sq;      // [nseg][n]   per-segment sum of squares             (Euclidean scale)
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
     WorkerQ* wq;          // [n]  written by the scale finalize

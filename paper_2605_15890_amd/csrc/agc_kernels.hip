@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
             double sum = 0.0;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) sum = sum + lds_acc[w][i];
-            a.part_sq[(int64_t)i * a.nseg + seg] = sum;
+            a.part_sq[seg * (int64_t)a.n + i] = sum;  // [segment][worker]: one coalesced row per workgroup
         }
     }
 }
@@ -208,6 +208,27 @@ __device__ __forceinline__ float inv16_of(float scale, int bits)
     return (q <= 3.402823466e+38f) ? q : 0.f;
 }
 
+// Euclidean scale, level 3 of the tree: one workgroup per group of 64 segments, thread t follows
+// worker t through the group's rows of [segment][worker] (coalesced) and adds them in segment order.
+__global__ __launch_bounds__(kWgThreads) void k_scale_groups(int n, Workspace ws)
+{
+    const int64_t g = blockIdx.x;
+    const int64_t s1 = (g + 1) * kGroupSegs < ws.nseg ? (g + 1) * kGroupSegs : ws.nseg;
+    for (int i = threadIdx.x; i < n; i += kWgThreads) {
+        const double* part = ws.part_sq + i;
+        double acc = 0.0;
+        for (int64_t s0 = g * kGroupSegs; s0 < s1; s0 += 8) {
+            double v[8];  // loads first, then the additions in segment order
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = s0 + u < s1 ? part[(s0 + u) * n] : 0.0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < s1) acc = acc + v[u];
+        }
+        ws.group_sq[(int64_t)i * ws.ngroup + g] = acc;
+    }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStreams out, StepWeights sw,
                                                                Workspace ws, float* scales)
@@ -233,22 +254,7 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
         }
         scale = __uint_as_float(red[0]);
     } else {
-        const double* part = ws.part_sq + (int64_t)i * ws.nseg;
-        // level 3: 64 segments -> group, in order
-        for (int64_t g = tid; g < ws.ngroup; g += kWgThreads) {
-            double acc = 0.0;
-            const int64_t s1 = (g + 1) * kGroupSegs < ws.nseg ? (g + 1) * kGroupSegs : ws.nseg;
-            for (int64_t s0 = g * kGroupSegs; s0 < s1; s0 += 8) {
-                double v[8];  // loads first, then the additions in segment order
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = s0 + u < s1 ? part[s0 + u] : 0.0;
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (s0 + u < s1) acc = acc + v[u];
-            }
-            ws.group_sq[(int64_t)i * ws.ngroup + g] = acc;
-        }
-        __syncthreads();
+        // level 3 (64 segments -> group) was formed by k_scale_groups
         // level 4: 64 groups -> supergroup, in order
         for (int64_t u = tid; u < ws.nsuper; u += kWgThreads) {
             double acc = 0.0;
@@ -284,9 +290,12 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
 hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
-    if (scale_mode == 0)
+    if (scale_mode == 0) {
+        hipLaunchKernelGGL(k_scale_groups, dim3((unsigned)ws.ngroup), dim3(kWgThreads), 0, stream, n, ws);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL((k_scale_finalize<0>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
-    else
+    } else
         hipLaunchKernelGGL((k_scale_finalize<1>), dim3(n), dim3(kWgThreads), 0, stream, n, out, sw, ws, scales);
     return hipGetLastError();
 }
