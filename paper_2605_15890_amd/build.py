@@ -10,7 +10,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libagc.so")
-SOURCES = ["agc_kernels.hip", "agc_quantize_b0.hip", "agc_quantize_b1.hip", "agc_quantize_b2.hip",
+SOURCES = ["agc_kernels.hip", "agc_quantize_b0s.hip", "agc_quantize_b0m.hip", "agc_quantize_b1s.hip",
+           "agc_quantize_b1m.hip", "agc_quantize_b2s.hip", "agc_quantize_b2m.hip",
            "agc_ls_kernels.hip", "agc_debug.hip", "agc_api.cpp", "agc_host.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

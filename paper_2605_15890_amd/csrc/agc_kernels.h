@@ -63,6 +63,19 @@ inline void stage_starts(const uint8_t* bits, int n, uint8_t* start)
         acc += bits[j];
     }
 }
+// number of fills the workers need
+inline int stage_fills(const uint8_t* bits, int n)
+{
+    int acc = 0, fills = n > 0 ? 1 : 0;
+    for (int j = 0; j < n; ++j) {
+        if (acc + bits[j] > kStageBits) {
+            acc = 0;
+            ++fills;
+        }
+        acc += bits[j];
+    }
+    return fills;
+}
 // largest fill over all groups, in bits (host side: sizes the LDS area of a launch)
 inline int stage_bits_needed(const uint8_t* bits, int n)
 {

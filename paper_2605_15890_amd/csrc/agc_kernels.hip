@@ -333,9 +333,12 @@ hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat, nullptr, stage_bits_needed(out.bits, n)};
-    return scale_mode == 0 ? launch_quantize_band2(G, code, ws, a, stream)
-                           : launch_quantize_band1(G, code, ws, a, stream);
+                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat, nullptr, stage_bits_needed(out.bits, n), stage_fills(out.bits, n)};
+    if (a.stage_fills > 1)
+        return scale_mode == 0 ? launch_quantize_band2m(G, code, ws, a, stream)
+                               : launch_quantize_band1m(G, code, ws, a, stream);
+    return scale_mode == 0 ? launch_quantize_band2s(G, code, ws, a, stream)
+                           : launch_quantize_band1s(G, code, ws, a, stream);
 }
 
 hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
@@ -343,8 +346,9 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            uint64_t step, float* ghat, hipStream_t stream)
 {
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                nullptr, 0, ghat, nullptr, stage_bits_needed(bits, n)};
-    return launch_quantize_band0(G, code, ws, a, stream);
+                nullptr, 0, ghat, nullptr, stage_bits_needed(bits, n), stage_fills(bits, n)};
+    return a.stage_fills > 1 ? launch_quantize_band0m(G, code, ws, a, stream)
+                             : launch_quantize_band0s(G, code, ws, a, stream);
 }
 
 // =======================================================================================

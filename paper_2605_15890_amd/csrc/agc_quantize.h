@@ -1,6 +1,7 @@
 // K2 of the worker side: streaming encode + stochastic quantize + bit-pack (+ the fused estimate).
-// Template code only; agc_quantize_b0/b1/b2.hip instantiate it for the three ways a block gets
-// its multiplier, so that the three sets of kernels compile in parallel.
+// Template code only; agc_quantize_b<0|1|2><s|m>.hip instantiate it for the three ways a block gets
+// its multiplier and for one or several fills of the staging area, so that the sets of kernels
+// compile in parallel.
 #pragma once
 
 #include "agc_device.h"
@@ -21,6 +22,7 @@ struct QuantArgs {
     float* ghat;    // fused step only
     const WindowRec* win;  // monotone-interval codes only; filled in by the launcher
     int stage_bits;        // largest sum of bit-widths one fill of the staging area holds (<= kStageBits)
+    int stage_fills;       // how many fills the workers need (1 unless the widths sum to more than kStageBits)
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
@@ -90,9 +92,13 @@ __device__ __forceinline__ float grid_pos(float f, float inv)
 // workgroup meets at a barrier and writes each worker's 128*b bytes as one contiguous, line-aligned
 // piece of its stream.  Stores of 64..96 bytes per wave and worker, as a wave alone would issue
 // them, reach memory as partial lines and cost several times their bytes on this memory system.
-template <int BUCKET, bool FUSE>
+// MULTI: the workers need more than one fill of the area, so it is also written out between
+// workers, inside the streaming loop.  Without MULTI (the common case: widths sum to at most
+// kStageBits) the loop over the workers contains no store at all and the kernel writes the area
+// out once, after the loop; the encode drivers then keep their rolling prefetch.
+template <int BUCKET, bool FUSE, bool MULTI>
 struct EpiQuant {
-    static constexpr bool kStoresPerWorker = true;  // stores may happen inside the worker loop (staging flush)
+    static constexpr bool kStoresPerWorker = MULTI;  // stores inside the worker loop (a flush between workers)
     static constexpr int kPrefetchRows = AGC_PREFETCH_ROWS;
     const WorkerQ* __restrict__ wq;
     uint32_t key0, key1, step_lo, step_hi;
@@ -332,11 +338,13 @@ struct EpiQuant {
             atomicOr(slot + 1, (uint32_t)(v >> 32));
             atomicOr(slot + 2, top);
         }
-        if (q.flush) flush_fill(i);  // wave-uniform, and the same for every wave of the workgroup
+        if constexpr (MULTI) {
+            if (q.flush) flush_fill(i);  // wave-uniform, and the same for every wave of the workgroup
+        }
     }
 };
 
-template <int S, int BUCKET, bool FUSE>
+template <int S, int BUCKET, bool FUSE, bool MULTI>
 // The compiler is told to plan for four waves per SIMD: with a register count just under the
 // five-wave limit it otherwise schedules for five and gives up instruction-level parallelism;
 // measured 1.45 ms against 1.51 ms on the metric workload (three: 1.51 ms).  The gather driver
@@ -375,16 +383,18 @@ __global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S
     const bool has_block = base < a.d;
     LaneCoords lc{};
     if (has_block) lc = lane_coords(base, lane, a.d);
-    EpiQuant<BUCKET, FUSE> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage,
+    EpiQuant<BUCKET, FUSE, MULTI> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage,
                                reinterpret_cast<float*>(lds_stage + 4 * stage_pieces(a.stage_bits)), lane, wave, a.n, wg,
                                groups_left >= 2 * kQuantWaves ? 2 * kQuantWaves : (int)groups_left, block, (uint32_t)((base + 4 * lane) >> 2),
                                lc.nvalid, lc.wave_ragged, 0u, 0u, a.scales, a.nb, 0, {0.f, 0.f, 0.f, 0.f},
                                load_uniform(wq)};
     if (!has_block) {  // nothing to encode, but the other waves of the workgroup wait at the flushes
-        epi.flush_only();
+        if constexpr (MULTI) epi.flush_only();
+        else epi.flush_fill(a.n - 1);
         return;
     }
     encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
+    if constexpr (!MULTI) epi.flush_fill(a.n - 1);  // the one fill: all workers, written out after the loop
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
         if (lc.nvalid == 4) {
@@ -397,7 +407,7 @@ __global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S
     }
 }
 
-template <int S, int BUCKET>
+template <int S, int BUCKET, bool MULTI>
 static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const Workspace& ws,
                                     const QuantArgs& args, hipStream_t stream)
 {
@@ -407,43 +417,48 @@ static hipError_t launch_quantize_s(const float* G, const CodeDev& code, const W
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const unsigned grid = (unsigned)((nblocks + kQuantWaves - 1) / kQuantWaves);
     if (a.stage_bits < 1 || a.stage_bits > kStageBits) return hipErrorInvalidValue;
+    if (MULTI ? a.stage_fills < 2 : a.stage_fills != 1) return hipErrorInvalidValue;
     const unsigned lds_bytes = 16u * (unsigned)stage_pieces(a.stage_bits) +
                                (BUCKET != 0 ? (unsigned)(sizeof(float) * kQuantWaves * a.n) : 0u);
+    const dim3 g(grid), b(kQuantThreads);
     if (a.ghat)
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, true>), dim3(grid), dim3(kQuantThreads), lds_bytes, stream, G,
-                           code.row_ptr, code.col, code.val, ws.wq, a);
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, true, MULTI>), g, b, lds_bytes, stream, G, code.row_ptr, code.col,
+                           code.val, ws.wq, a);
     else
-        hipLaunchKernelGGL((k_quantize<S, BUCKET, false>), dim3(grid), dim3(kQuantThreads), lds_bytes, stream, G,
-                           code.row_ptr, code.col, code.val, ws.wq, a);
+        hipLaunchKernelGGL((k_quantize<S, BUCKET, false, MULTI>), g, b, lds_bytes, stream, G, code.row_ptr, code.col,
+                           code.val, ws.wq, a);
     return hipGetLastError();
 }
 
-template <int BUCKET>
+template <int BUCKET, bool MULTI>
 static inline hipError_t launch_quantize_band(const float* G, const CodeDev& code, const Workspace& ws,
-                                       const QuantArgs& a, hipStream_t stream)
+                                              const QuantArgs& a, hipStream_t stream)
 {
     switch (code.band) {
-        case 1: return launch_quantize_s<1, BUCKET>(G, code, ws, a, stream);
-        case 2: return launch_quantize_s<2, BUCKET>(G, code, ws, a, stream);
-        case 3: return launch_quantize_s<3, BUCKET>(G, code, ws, a, stream);
-        case 4: return launch_quantize_s<4, BUCKET>(G, code, ws, a, stream);
-        case 5: return launch_quantize_s<5, BUCKET>(G, code, ws, a, stream);
-        case 6: return launch_quantize_s<6, BUCKET>(G, code, ws, a, stream);
-        case 7: return launch_quantize_s<7, BUCKET>(G, code, ws, a, stream);
-        case 8: return launch_quantize_s<8, BUCKET>(G, code, ws, a, stream);
-        case -2: return launch_quantize_s<-2, BUCKET>(G, code, ws, a, stream);
-        case -4: return launch_quantize_s<-4, BUCKET>(G, code, ws, a, stream);
-        case -8: return launch_quantize_s<-8, BUCKET>(G, code, ws, a, stream);
-        default: return launch_quantize_s<0, BUCKET>(G, code, ws, a, stream);
+        case 1: return launch_quantize_s<1, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 2: return launch_quantize_s<2, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 3: return launch_quantize_s<3, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 4: return launch_quantize_s<4, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 5: return launch_quantize_s<5, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 6: return launch_quantize_s<6, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 7: return launch_quantize_s<7, BUCKET, MULTI>(G, code, ws, a, stream);
+        case 8: return launch_quantize_s<8, BUCKET, MULTI>(G, code, ws, a, stream);
+        case -2: return launch_quantize_s<-2, BUCKET, MULTI>(G, code, ws, a, stream);
+        case -4: return launch_quantize_s<-4, BUCKET, MULTI>(G, code, ws, a, stream);
+        case -8: return launch_quantize_s<-8, BUCKET, MULTI>(G, code, ws, a, stream);
+        default: return launch_quantize_s<0, BUCKET, MULTI>(G, code, ws, a, stream);
     }
 }
 
-// one entry point per instantiation unit
-hipError_t launch_quantize_band0(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
-                                 hipStream_t stream);
-hipError_t launch_quantize_band1(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
-                                 hipStream_t stream);
-hipError_t launch_quantize_band2(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a,
-                                 hipStream_t stream);
+// One entry point per instantiation unit (agc_quantize_b<BUCKET><s|m>.hip: the way a block gets its
+// multiplier, and one fill or several), so that the sets of kernels compile in parallel.
+#define AGC_QUANT_UNIT(NAME) \
+    hipError_t NAME(const float* G, const CodeDev& code, const Workspace& ws, const QuantArgs& a, hipStream_t stream)
+AGC_QUANT_UNIT(launch_quantize_band0s);
+AGC_QUANT_UNIT(launch_quantize_band0m);
+AGC_QUANT_UNIT(launch_quantize_band1s);
+AGC_QUANT_UNIT(launch_quantize_band1m);
+AGC_QUANT_UNIT(launch_quantize_band2s);
+AGC_QUANT_UNIT(launch_quantize_band2m);
 
 }  // namespace agc

@@ -1,0 +1,11 @@
+// K2 kernels, one max-abs scale per 256-coordinate block, found in the pass; all workers fit one fill of the staging area.
+#include "agc_quantize.h"
+
+namespace agc {
+
+AGC_QUANT_UNIT(launch_quantize_band1s)
+{
+    return launch_quantize_band<1, false>(G, code, ws, a, stream);
+}
+
+}  // namespace agc
