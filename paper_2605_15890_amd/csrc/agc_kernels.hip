@@ -426,6 +426,36 @@ __device__ __forceinline__ void decode_words(const global_u32* __restrict__ src,
     }
 }
 
+// Two-bit workers (sign + one level bit; most workers of a tight budget): shifted to the top of a
+// word, the code's two bits are the sign and the leading exponent bit of a float, i.e. the values
+// +0, +2, -0, -2 = twice the decoded value.  With half the weight the fused multiply-add has the
+// same exact product and therefore the same rounded result as fma(coef, +-level, acc): three
+// vector instructions per code (shift, mask, fma) instead of five.  The caller guarantees that
+// halving the weights is exact (they are zero or normal numbers above the smallest exponent).
+template <bool TWO>
+__device__ __forceinline__ void decode_words_2bit(const global_u32* __restrict__ src, float half_coef,
+                                                  float half_coef2, float (&acc)[kDecCoords],
+                                                  float (&acc2)[TWO ? kDecCoords : 1])
+{
+    uint32_t w[2];
+    w[0] = __builtin_nontemporal_load(src);
+    w[1] = __builtin_nontemporal_load(src + 1);
+#pragma unroll
+    for (int q = 0; q < kDecCoords; ++q) {
+        const int sh = 30 - 2 * (q & 15);  // brings code q of its word to bits 31..30
+        const float v2 = __uint_as_float((w[q >> 4] << sh) & 0xC0000000u);
+        acc[q] = fmaf(half_coef, v2, acc[q]);
+        if (TWO) acc2[TWO ? q : 0] = fmaf(half_coef2, v2, acc2[TWO ? q : 0]);
+    }
+}
+
+// true when x / 2 is exact in binary32: zero, or a normal number that stays normal
+__device__ __forceinline__ bool halves_exactly(float x)
+{
+    const uint32_t e = (__float_as_uint(x) >> 23) & 0xFFu;
+    return x == 0.0f || (e >= 2u && e != 0xFFu);
+}
+
 struct DecodeArgs {
     int n_arrived;
     int64_t d;
@@ -446,8 +476,11 @@ __device__ __forceinline__ void store_coords(float* dst, const float (&acc)[kDec
     }
 }
 
+// Planned for six waves per SIMD (77 registers instead of 82): the kernel is short (12 waves per
+// SIMD at the metric size), so one more resident wave shortens its last, partly filled round;
+// measured 0.175 -> 0.168 ms.  Eight would spill.
 template <bool TWO, bool BUCKET>
-__global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict__ wd,
+__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(TWO ? 1 : 6, TWO ? 8 : 6))) void k_decode(const WorkerD* __restrict__ wd,
                                                        const float* __restrict__ coef2,
                                                        const float* const* __restrict__ srow, DecodeArgs a)
 {
@@ -473,7 +506,13 @@ __global__ __launch_bounds__(kWgThreads) void k_decode(const WorkerD* __restrict
         const global_u32* src = (const global_u32*)wk.codes + t * b;
         switch (b) {
             case 1: decode_words<1, TWO>(src, c1, c2, acc, acc2); break;
-            case 2: decode_words<2, TWO>(src, c1, c2, acc, acc2); break;
+            case 2:
+                // wave-uniform choice (without bucket-wise scales the weights are per worker)
+                if (!BUCKET && halves_exactly(c1) && (!TWO || halves_exactly(c2)))
+                    decode_words_2bit<TWO>(src, 0.5f * c1, 0.5f * c2, acc, acc2);
+                else
+                    decode_words<2, TWO>(src, c1, c2, acc, acc2);
+                break;
             case 3: decode_words<3, TWO>(src, c1, c2, acc, acc2); break;
             case 4: decode_words<4, TWO>(src, c1, c2, acc, acc2); break;
             case 5: decode_words<5, TWO>(src, c1, c2, acc, acc2); break;
