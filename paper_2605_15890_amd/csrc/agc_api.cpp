@@ -209,6 +209,9 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     } else if (o.scale_mode == AGC_SCALE_MAXABS) {
         e = dev_alloc(&c->ws.part_max, (size_t)agc::kMaxSlots * n);
         if (e == hipSuccess) e = hipMemset(c->ws.part_max, 0, sizeof(uint32_t) * (size_t)agc::kMaxSlots * n);
+        // the first scale pass may run on any stream of the caller, also one that does not order
+        // itself after the default stream: the zeros must be in memory before this call returns
+        if (e == hipSuccess) e = hipDeviceSynchronize();
     } else {
         e = dev_alloc(&c->ws.part_sq, (size_t)c->ws.nseg * n);
         if (e == hipSuccess) e = dev_alloc(&c->ws.group_sq, (size_t)c->ws.ngroup * n);
