@@ -172,7 +172,11 @@ __device__ __forceinline__ float4 load_row4(const float* __restrict__ row, const
     typedef const __attribute__((address_space(1))) char* global_bytes_t;
     typedef const __attribute__((address_space(1))) f32x4_t* global_f32x4_t;
     const global_f32x4_t src = (global_f32x4_t)((global_bytes_t)row + lc.byte_off);
+#ifdef AGC_PLAIN_ROW_LOADS
+    const f32x4_t t = *src;
+#else
     const f32x4_t t = STREAM ? __builtin_nontemporal_load(src) : *src;
+#endif
     float4 v = make_float4(t.x, t.y, t.z, t.w);
     if (RAGGED) {
         if (lc.nvalid < 1) v.x = 0.f;
@@ -192,9 +196,47 @@ __device__ __forceinline__ float4 fma4(float a, const float4& g, const float4& c
     return make_float4(fmaf(a, g.x, c.x), fmaf(a, g.y, c.y), fmaf(a, g.z, c.z), fmaf(a, g.w, c.w));
 }
 
+// What a lane holds of one row of G while it streams through a register ring: its float4 of one
+// block (float4 itself), or its float4s of two neighbouring blocks (Row2; the wave then covers 512
+// consecutive coordinates and issues two loads per row, 1 KiB apart).  The two-block form halves
+// the number of row walks and of per-worker reductions; it is used where registers allow it (the
+// max-abs scale pass).  Both forms perform the same arithmetic on every coordinate.
+struct Row2 {
+    float4 a, b;
+};
+__device__ __forceinline__ Row2 mul4(float c, const Row2& g) { return Row2{mul4(c, g.a), mul4(c, g.b)}; }
+__device__ __forceinline__ Row2 fma4(float c, const Row2& g, const Row2& f)
+{
+    return Row2{fma4(c, g.a, f.a), fma4(c, g.b, f.b)};
+}
+
+template <class Row>
+__device__ __forceinline__ Row zero_row();
+template <>
+__device__ __forceinline__ float4 zero_row<float4>() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+template <>
+__device__ __forceinline__ Row2 zero_row<Row2>()
+{
+    return Row2{make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+}
+
+// streaming load of a lane's part of a row whose blocks lie wholly inside the vector
+template <class Row>
+__device__ __forceinline__ Row load_row(const float* __restrict__ row, const LaneCoords& lc);
+template <>
+__device__ __forceinline__ float4 load_row<float4>(const float* __restrict__ row, const LaneCoords& lc)
+{
+    return load_row4<false, true>(row, lc);
+}
+template <>
+__device__ __forceinline__ Row2 load_row<Row2>(const float* __restrict__ row, const LaneCoords& lc)
+{
+    return Row2{load_row4<false, true>(row, lc), load_row4<false, true>(row + kBlockCoords, lc)};
+}
+
 // ---------------------------------------------------------------------------------------
 // Encode driver 1: cyclic band.  n == k, worker i stores columns (i+u) mod k, u = 0..S-1.
-// Rows stream once through a ring of R = S + P float4 registers (P rows of prefetch); worker
+// Rows stream once through a ring of R = S + P row registers (P rows of prefetch); worker
 // i is formed when row i+S-1 has arrived.  The first S-1 rows are kept in a register stash
 // for the last S-1 workers, which wrap around, so every element of G is read exactly once.
 // R is even so that the parity of the worker handled at each unrolled position is known at
@@ -222,20 +264,24 @@ __device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)
 {
     return make_float4(c ? a.x : b.x, c ? a.y : b.y, c ? a.z : b.z, c ? a.w : b.w);
 }
+__device__ __forceinline__ Row2 sel4(bool c, const Row2& a, const Row2& b)
+{
+    return Row2{sel4(c, a.a, b.a), sel4(c, a.b, b.b)};
+}
 
 // stash helpers with compile-time indices (so the stash stays in registers)
-template <int S, int PF, int... Us>
-__device__ __forceinline__ float4 stash_pick(const float4 (&stash)[(RingShapeT<S, PF>::NSTASH)], int idx,
+template <int S, int PF, class Row, int... Us>
+__device__ __forceinline__ Row stash_pick(const Row (&stash)[(RingShapeT<S, PF>::NSTASH)], int idx,
                                              std::integer_sequence<int, Us...>)
 {
-    float4 v = stash[0];
+    Row v = stash[0];
     ((v = sel4(idx == Us + 1, stash[(Us + 1) < RingShapeT<S, PF>::NSTASH ? (Us + 1) : 0], v)), ...);
     return v;
 }
 
-template <int S, int PF, int r, int... Us>
-__device__ __forceinline__ void stash_fill(float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
-                                           const float4 (&ring)[(RingShapeT<S, PF>::R)],
+template <int S, int PF, class Row, int r, int... Us>
+__device__ __forceinline__ void stash_fill(Row (&stash)[(RingShapeT<S, PF>::NSTASH)],
+                                           const Row (&ring)[(RingShapeT<S, PF>::R)],
                                            std::integer_sequence<int, Us...>)
 {
     constexpr int R = RingShapeT<S, PF>::R;
@@ -247,9 +293,9 @@ __device__ __forceinline__ void stash_fill(float4 (&stash)[(RingShapeT<S, PF>::N
 // is valid and no wrapped row is involved, so the compiler can count outstanding loads exactly
 // and let P of them stay in flight.  The first round and the last one or two (GENERAL) carry
 // the conditions: workers that do not exist yet, the stash fill, the wrapped rows.
-template <int S, int PF, int r, bool STEADY, class Epi>
-__device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)],
-                                          float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
+template <int S, int PF, class Row, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void ring_step(Row (&ring)[(RingShapeT<S, PF>::R)],
+                                          Row (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                           const float*& next_row, int64_t ldg, int k,
                                           const float* __restrict__ bval, const LaneCoords& lc,
                                           int j0, float (&coef)[S], Epi& epi)
@@ -258,27 +304,27 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)]
     constexpr int R = RingShapeT<S, PF>::R;
     const int j = j0 + r;
     if (STEADY) {
-        ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
+        ring[(r + P) % R] = load_row<Row>(next_row, lc);
         next_row += (j + P + 1 < k) ? ldg : 0;  // stays on the last row once it is reached
     } else {
         if (j + P < k) {  // prefetch the row that arrives P steps from now
-            ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
+            ring[(r + P) % R] = load_row<Row>(next_row, lc);
             next_row += (j + P + 1 < k) ? ldg : 0;
         }
         if (S > 1 && j >= k && j < k + S - 1)  // arrivals k..k+S-2 are rows 0..S-2, kept in the stash
-            ring[r] = stash_pick<S, PF>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
+            ring[r] = stash_pick<S, PF, Row>(stash, j - k, std::make_integer_sequence<int, (S > 2 ? S - 2 : 0)>{});
     }
     const int i = j - (S - 1);
     if (STEADY || (i >= 0 && i < k)) {
         if (!STEADY && S > 1 && i == 0)
-            stash_fill<S, PF, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
+            stash_fill<S, PF, Row, r>(stash, ring, std::make_integer_sequence<int, (S > 1 ? S - 1 : 0)>{});
         // the worker's coefficients were requested one worker earlier (the scalar read is then
         // over by the time they are used); request the next worker's now
         float next[S];
         const float* bv = bval + (int64_t)(i + 1 < k ? i + 1 : i) * S;
 #pragma unroll
         for (int u = 0; u < S; ++u) next[u] = bv[u];
-        float4 f = mul4(coef[0], ring[(r + R - (S - 1)) % R]);
+        Row f = mul4(coef[0], ring[(r + R - (S - 1)) % R]);
 #pragma unroll
         for (int u = 1; u < S; ++u) f = fma4(coef[u], ring[(r + R - (S - 1) + u) % R], f);
         epi.template worker<(((r + R - (S - 1)) & 1) == 0)>(i, f);
@@ -287,17 +333,17 @@ __device__ __forceinline__ void ring_step(float4 (&ring)[(RingShapeT<S, PF>::R)]
     }
 }
 
-template <int S, int PF, bool STEADY, class Epi, int... Rs>
-__device__ __forceinline__ void ring_round(float4 (&ring)[(RingShapeT<S, PF>::R)],
-                                           float4 (&stash)[(RingShapeT<S, PF>::NSTASH)],
+template <int S, int PF, class Row, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void ring_round(Row (&ring)[(RingShapeT<S, PF>::R)],
+                                           Row (&stash)[(RingShapeT<S, PF>::NSTASH)],
                                            const float*& next_row, int64_t ldg, int k,
                                            const float* __restrict__ bval, const LaneCoords& lc,
                                            int j0, float (&coef)[S], Epi& epi, std::integer_sequence<int, Rs...>)
 {
-    (ring_step<S, PF, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi), ...);
+    (ring_step<S, PF, Row, Rs, STEADY>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi), ...);
 }
 
-template <int S, int PF, class Epi>
+template <int S, int PF, class Row, class Epi>
 __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t ldg, int k,
                                             const float* __restrict__ bval, const LaneCoords& lc,
                                             Epi& epi)
@@ -307,16 +353,16 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
     static_assert(R % 2 == 0, "ring length must be even");
     constexpr auto seq = std::make_integer_sequence<int, R>{};
     const int steps = k + S - 1;  // row arrivals, the last S-1 being the wrapped rows
-    float4 ring[R];
-    float4 stash[(RingShapeT<S, PF>::NSTASH)];
+    Row ring[R];
+    Row stash[(RingShapeT<S, PF>::NSTASH)];
     const float* next_row = G;  // G already points at the block's first coordinate in row 0
 #pragma unroll
-    for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-    stash[0] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = 0; r < R; ++r) ring[r] = zero_row<Row>();
+    stash[0] = zero_row<Row>();
 #pragma unroll
     for (int r = 0; r < P; ++r) {
         if (r < k) {
-            ring[r] = load_row4<false, true>(next_row, lc);
+            ring[r] = load_row<Row>(next_row, lc);
             next_row += (r + 1 < k) ? ldg : 0;
         }
     }
@@ -324,11 +370,11 @@ __device__ __forceinline__ void encode_ring(const float* __restrict__ G, int64_t
 #pragma unroll
     for (int u = 0; u < S; ++u) coef[u] = bval[u];
     int j0 = 0;
-    ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
+    ring_round<S, PF, Row, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
     for (j0 = R; j0 + R - 1 < k; j0 += R)
-        ring_round<S, PF, true>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
+        ring_round<S, PF, Row, true>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
     for (; j0 < steps; j0 += R)
-        ring_round<S, PF, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
+        ring_round<S, PF, Row, false>(ring, stash, next_row, ldg, k, bval, lc, j0, coef, epi, seq);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -415,8 +461,8 @@ __device__ __forceinline__ WindowCur load_window_rec(const WindowRec* rec)
     return c;
 }
 
-template <int W, int PF, int r, bool STEADY, class Epi>
-__device__ __forceinline__ void window_step(float4 (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
+template <int W, int PF, class Row, int r, bool STEADY, class Epi>
+__device__ __forceinline__ void window_step(Row (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
                                             int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
                                             int j0, int& i, WindowCur& cur, Epi& epi)
 {
@@ -424,13 +470,13 @@ __device__ __forceinline__ void window_step(float4 (&ring)[(RingShapeT<W, PF>::R
     constexpr int R = RingShapeT<W, PF>::R;
     const int j = j0 + r;
     if (STEADY || j + P < k) {  // prefetch the row that arrives P steps from now
-        ring[(r + P) % R] = load_row4<false, true>(next_row, lc);
+        ring[(r + P) % R] = load_row<Row>(next_row, lc);
         next_row += (j + P + 1 < k) ? ldg : 0;
     }
     const int lo = j - (W - 1);
     while (cur.lo == lo) {  // the sentinel record ends the last run
         const WindowCur nxt = load_window_rec(B.win + i + 1);
-        float4 f = mul4(cur.val[0], ring[(r + R - (W - 1)) % R]);
+        Row f = mul4(cur.val[0], ring[(r + R - (W - 1)) % R]);
 #pragma unroll
         for (int u = 1; u < W; ++u)
             if (u < cur.len) f = fma4(cur.val[u], ring[(r + R - (W - 1) + u) % R], f);
@@ -440,30 +486,30 @@ __device__ __forceinline__ void window_step(float4 (&ring)[(RingShapeT<W, PF>::R
     }
 }
 
-template <int W, int PF, bool STEADY, class Epi, int... Rs>
-__device__ __forceinline__ void window_round(float4 (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
+template <int W, int PF, class Row, bool STEADY, class Epi, int... Rs>
+__device__ __forceinline__ void window_round(Row (&ring)[(RingShapeT<W, PF>::R)], const float*& next_row,
                                              int64_t ldg, int k, const CsrView& B, const LaneCoords& lc,
                                              int j0, int& i, WindowCur& cur, Epi& epi,
                                              std::integer_sequence<int, Rs...>)
 {
-    (window_step<W, PF, Rs, STEADY>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi), ...);
+    (window_step<W, PF, Row, Rs, STEADY>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi), ...);
 }
 
-template <int W, int PF, class Epi>
+template <int W, int PF, class Row, class Epi>
 __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64_t ldg, int k,
                                               const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     constexpr int P = RingShapeT<W, PF>::P;
     constexpr int R = RingShapeT<W, PF>::R;
     constexpr auto seq = std::make_integer_sequence<int, R>{};
-    float4 ring[R];
+    Row ring[R];
     const float* next_row = G;
 #pragma unroll
-    for (int r = 0; r < R; ++r) ring[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = 0; r < R; ++r) ring[r] = zero_row<Row>();
 #pragma unroll
     for (int r = 0; r < P; ++r) {
         if (r < k) {
-            ring[r] = load_row4<false, true>(next_row, lc);
+            ring[r] = load_row<Row>(next_row, lc);
             next_row += (r + 1 < k) ? ldg : 0;
         }
     }
@@ -472,9 +518,9 @@ __device__ __forceinline__ void encode_window(const float* __restrict__ G, int64
     int j0 = 0;
     const int steps = k + W - 1;  // the last worker may be anchored at row k-1
     for (; j0 + R - 1 + P < k; j0 += R)  // every prefetch of the round exists
-        window_round<W, PF, true>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
+        window_round<W, PF, Row, true>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
     for (; j0 < steps; j0 += R)
-        window_round<W, PF, false>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
+        window_round<W, PF, Row, false>(ring, next_row, ldg, k, B, lc, j0, i, cur, epi, seq);
 }
 
 // The same driver for epilogues that store inside the worker loop (the quantize pass).  Stores
@@ -577,12 +623,12 @@ __device__ __forceinline__ void encode_block(const float* __restrict__ G, int64_
                                              const CsrView& B, const LaneCoords& lc, Epi& epi)
 {
     if constexpr (S > 0) {
-        if (!lc.wave_ragged) encode_ring<S, Epi::kPrefetchRows>(G, ldg, k, B.val, lc, epi);
+        if (!lc.wave_ragged) encode_ring<S, Epi::kPrefetchRows, float4>(G, ldg, k, B.val, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);
     } else if constexpr (S < 0) {  // monotone intervals of at most -S columns
         if (lc.wave_ragged) encode_gather<true>(G, ldg, n, B, lc, epi);
         else if constexpr (Epi::kStoresPerWorker) encode_window_batched<-S>(G, ldg, k, B, lc, epi);
-        else encode_window<-S, Epi::kPrefetchRows>(G, ldg, k, B, lc, epi);
+        else encode_window<-S, Epi::kPrefetchRows, float4>(G, ldg, k, B, lc, epi);
     } else {
         if (!lc.wave_ragged) encode_gather<false>(G, ldg, n, B, lc, epi);
         else encode_gather<true>(G, ldg, n, B, lc, epi);

@@ -47,14 +47,24 @@ struct EpiMaxAbs {
     static constexpr int kPrefetchRows = AGC_SCALE_PREFETCH_ROWS;
     uint32_t* acc;  // this wave's LDS slice [n], bit patterns of non-negative floats
     int lane;
+    static __device__ __forceinline__ float max_abs4(const float4& f)
+    {
+        return fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+    }
     template <bool EVEN>
     __device__ __forceinline__ void worker(int i, const float4& f)
     {
-        const float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
-        const uint32_t m = wave_max_nonneg_bits(a);
+        const uint32_t m = wave_max_nonneg_bits(max_abs4(f));
         if (lane == 0) acc[i] = m;
     }
-    __device__ __forceinline__ void worker_any(int i, const float4& f) { worker<true>(i, f); }
+    template <bool EVEN>
+    __device__ __forceinline__ void worker(int i, const Row2& f)  // two blocks, one reduction
+    {
+        const uint32_t m = wave_max_nonneg_bits(fmaxf(max_abs4(f.a), max_abs4(f.b)));
+        if (lane == 0) acc[i] = m;
+    }
+    template <class Row>
+    __device__ __forceinline__ void worker_any(int i, const Row& f) { worker<true>(i, f); }
 };
 
 // epilogue for the Euclidean scale: levels 0 and 1 of the binary64 summation tree (lane value
@@ -76,65 +86,87 @@ struct EpiSumSq {
     __device__ __forceinline__ void worker_any(int i, const float4& f) { worker<true>(i, f); }
 };
 
-// One workgroup per 1024-coordinate segment, one wave per 256-coordinate block of it.
-// Euclidean scale: the four block values of every worker meet in LDS and are combined in block
-// order (level 2 of the tree), which keeps the result independent of how the waves were
-// scheduled.  Max-abs scale: the maximum is exact and order-free, so every wave folds its block's
-// n maxima into one of kMaxSlots rows of a small array ([slot][worker], slot = block mod
-// kMaxSlots) with one integer atomic-max instruction (bit patterns of non-negative floats order
-// like the floats) and leaves; nothing waits, and the pass writes no partial results to memory
-// (stores mixed into the read stream cost far more than their bytes on this memory system).
-// The finalize kernel reads the rows and hands them back zeroed.
-template <int S, int MODE, int WAVES>
+// The norm's workgroups are the four blocks of a segment of its summation tree; the max-abs pass
+// is free in its workgroup size (4 and 8 waves measured within 1 % of each other, 16 waves 2 %
+// slower) and, with two blocks per wave, in its prefetch distance (2 to 8 rows within 1 %).
+#ifndef AGC_SCALE_WAVES
+#define AGC_SCALE_WAVES 8
+#endif
+#ifndef AGC_SCALE_PREFETCH_ROWS2
+#define AGC_SCALE_PREFETCH_ROWS2 2  // rows ahead in the two-block ring: four loads in flight per lane
+#endif
+// below this many blocks the two-block form would leave compute units without a wave
+// (256 units x 4 SIMDs x 5 resident waves of two blocks each, twice over)
+constexpr int64_t kTwoBlockMin = 2 * 2 * 256 * 4 * 5;
+// Euclidean scale: one workgroup per 1024-coordinate segment, one wave per 256-coordinate block of
+// it.  The four block values of every worker meet in LDS and are combined in block order (level 2
+// of the tree), which keeps the result independent of how the waves were scheduled.
+// Max-abs scale: the maximum is exact and order-free.  A wave takes V neighbouring blocks (V = 2:
+// both at once through the two-block register ring when they lie wholly inside the vector and the
+// code has a ring driver, else one after the other), folds the n maxima into one of kMaxSlots
+// rows of a small array ([slot][worker]) with one integer atomic-max instruction (bit patterns of
+// non-negative floats order like the floats) and leaves; nothing waits, and the pass writes no
+// partial results to memory (stores mixed into the read stream cost far more than their bytes on
+// this memory system).  The finalize kernel reads the rows and hands them back zeroed.
+template <int S, int MODE, int WAVES, int V>
 __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __restrict__ G,
                                                               const int* __restrict__ row_ptr,
                                                               const int* __restrict__ col,
                                                               const float* __restrict__ val,
                                                               ScaleArgs a)
 {
-    static_assert(MODE == 1 || WAVES == kSegBlocks, "the norm's tree fixes four blocks per workgroup");
+    static_assert(MODE == 1 || (WAVES == kSegBlocks && V == 1), "the norm's tree fixes four blocks per workgroup");
+    static_assert(V == 1 || V == 2, "one or two blocks per wave");
     __shared__ double lds_acc[WAVES][kMaxWorkers];
     // the wave index is the same for all lanes: tell the compiler, so that everything derived
     // from it (block base, pointers) lives in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int64_t seg = blockIdx.x;
-    const int64_t blk = seg * WAVES + wave;
-    const int64_t base = blk * (int64_t)kBlockCoords;
+    const int64_t blk = seg * WAVES + wave;  // max-abs: index of the wave's run of V blocks
+    const int64_t base = blk * (int64_t)(V * kBlockCoords);
+    const CsrView B{row_ptr, col, val, a.win};
 
     double* accd = lds_acc[wave];
     uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
-    if (base < a.d) {
-        const LaneCoords lc = lane_coords(base, lane, a.d);
-        if (MODE == 0) {
-            EpiSumSq epi{accd, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
-        } else {
-            EpiMaxAbs epi{accu, lane};
-            encode_block<S>(G + base, a.ldg, a.n, a.k, CsrView{row_ptr, col, val, a.win}, lc, epi);
-        }
-    } else {  // a block past the end of the vector contributes nothing
-        for (int i = lane; i < a.n; i += kWave) {
-            if (MODE == 0) accd[i] = 0.0;
-            else accu[i] = 0u;
-        }
-    }
     if (MODE == 1) {
-        if (base < a.d) {
-            uint32_t* dst = a.part_max + (blk & (kMaxSlots - 1)) * a.n;
-            for (int i = lane; i < a.n; i += kWave)  // accu[i] was written by this wave's lane 0
+        if (base >= a.d) return;
+        uint32_t* dst = a.part_max + (blk & (kMaxSlots - 1)) * a.n;
+        EpiMaxAbs epi{accu, lane};
+        auto fold = [&]() {  // accu[i] was written by this wave's lane 0
+            for (int i = lane; i < a.n; i += kWave)
                 (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        if (V == 2 && S != 0 && base + 2 * kBlockCoords <= a.d) {
+            const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in both blocks
+            if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, val, lc, epi);
+            else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, B, lc, epi);
+            fold();
+        } else {
+            for (int u = 0; u < V; ++u) {
+                const int64_t b = base + (int64_t)u * kBlockCoords;
+                if (b < a.d) {
+                    const LaneCoords lc = lane_coords(b, lane, a.d);
+                    encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
+                    fold();
+                }
+            }
         }
         return;
     }
+    if (base < a.d) {
+        const LaneCoords lc = lane_coords(base, lane, a.d);
+        EpiSumSq epi{accd, lane};
+        encode_block<S>(G + base, a.ldg, a.n, a.k, B, lc, epi);
+    } else {  // a block past the end of the vector contributes nothing
+        for (int i = lane; i < a.n; i += kWave) accd[i] = 0.0;
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < a.n; i += kWave * WAVES) {
-        if (MODE == 0) {
-            double sum = 0.0;
+        double sum = 0.0;
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) sum = sum + lds_acc[w][i];
-            a.part_sq[seg * (int64_t)a.n + i] = sum;  // [segment][worker]: one coalesced row per workgroup
-        }
+        for (int w = 0; w < WAVES; ++w) sum = sum + lds_acc[w][i];
+        a.part_sq[seg * (int64_t)a.n + i] = sum;  // [segment][worker]: one coalesced row per workgroup
     }
 }
 
@@ -154,23 +186,32 @@ hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stre
     return hipGetLastError();
 }
 
-// The norm's workgroups are the four blocks of a segment of its summation tree; the max-abs pass
-// is free in its workgroup size (4, 8 and 16 waves measured within 0.5 % of each other).
-#ifndef AGC_SCALE_WAVES
-#define AGC_SCALE_WAVES 4
+#ifndef AGC_SCALE_BLOCKS_PER_WAVE
+#define AGC_SCALE_BLOCKS_PER_WAVE 2
 #endif
+template <int S, int V>
+static void launch_scale_max(const float* G, const CodeDev& code, const ScaleArgs& a, hipStream_t stream)
+{
+    constexpr int W = AGC_SCALE_WAVES;
+    const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
+    const int64_t per_wg = (int64_t)W * V;
+    hipLaunchKernelGGL((k_scale_pass<S, 1, W, V>), dim3((unsigned)((nblocks + per_wg - 1) / per_wg)), dim3(kWave * W),
+                       0, stream, G, code.row_ptr, code.col, code.val, a);
+}
+
 template <int S>
 static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const ScaleArgs& a,
                                       int scale_mode, hipStream_t stream)
 {
     if (scale_mode == 0) {
-        hipLaunchKernelGGL((k_scale_pass<S, 0, kSegBlocks>), dim3((unsigned)a.nseg), dim3(kWgThreads), 0, stream, G,
+        hipLaunchKernelGGL((k_scale_pass<S, 0, kSegBlocks, 1>), dim3((unsigned)a.nseg), dim3(kWgThreads), 0, stream, G,
                            code.row_ptr, code.col, code.val, a);
     } else {
-        constexpr int W = AGC_SCALE_WAVES;
+        // two blocks per wave where a ring driver serves the code and the vector is long enough
+        // to fill the chip with half as many waves
         const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
-        hipLaunchKernelGGL((k_scale_pass<S, 1, W>), dim3((unsigned)((nblocks + W - 1) / W)), dim3(kWave * W), 0, stream,
-                           G, code.row_ptr, code.col, code.val, a);
+        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE == 2 && nblocks >= kTwoBlockMin) launch_scale_max<S, 2>(G, code, a, stream);
+        else launch_scale_max<S, 1>(G, code, a, stream);
     }
     return hipGetLastError();
 }

@@ -368,6 +368,8 @@ __global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S
         const int64_t per = gridDim.x / 8;
         if (wg < per * 8) wg = (wg % 8) * per + wg / 8;
     }
+#elif defined(AGC_REVERSE_ORDER)
+    const int64_t wg = (int64_t)gridDim.x - 1 - blockIdx.x;
 #else
     const int64_t wg = blockIdx.x;
 #endif

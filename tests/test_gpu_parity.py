@@ -411,3 +411,41 @@ def test_paper_interval_code_on_named_configs(name):
                             out, tag=f"{name} interval generic={force_generic}")
         outs.append(out)
     assert all(np.array_equal(a, b) for a, b in zip(outs[0][0], outs[1][0]))
+
+
+# ---------------------------------------------------------------------------------------------
+# Max-abs scale pass, two blocks of 256 coordinates per wave (engaged from 20480 blocks on, for
+# codes served by a register-ring driver): whole step against the oracle at sizes whose tail is
+# a lone full block, a full block followed by a ragged one, or a ragged first block of a pair;
+# each row of G carries one dominant entry at a place that only one part of the kernel sees.
+# ---------------------------------------------------------------------------------------------
+TWO_BLOCK_MIN = 20480
+
+
+@pytest.mark.parametrize("kind", ["cyclic3", "window4"])
+@pytest.mark.parametrize("tail", [0, 256, 300, 513, 767])
+def test_two_block_scale_pass_matches_oracle(kind, tail):
+    rng = np.random.default_rng(4100 + tail)
+    d = TWO_BLOCK_MIN * 256 + tail
+    if kind == "cyclic3":
+        n = k = 5
+        row_ptr, col, val = cyclic_csr(rng, n, 3)
+        path = 3
+    else:
+        n, k = 6, 5
+        row_ptr, col, val = monotone_csr(rng, n, k, 4)
+        path = None
+    G_host = (rng.standard_normal((k, d)) * 0.01).astype(np.float32)
+    # dominant entries: second block of a pair, last coordinate, the block before the tail,
+    # first block of the last whole pair, a middle pair's second block
+    spots = [300, d - 1, (d - 1) // 256 * 256 - 3, (d // 512 - 1) * 512 + 17, 512 * 4097 + 511]
+    for j in range(k):
+        G_host[j, spots[j % len(spots)]] = np.float32(3.0 + j)
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = (rng.uniform(size=n) < 0.8).astype(np.uint8)
+    mask[0] = 1
+    G = to_device(G_host)
+    out = run_hip(G, n, k, d, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_MAXABS, expect_path=path)
+    compare_with_oracle(G_host, k, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_MAXABS, out,
+                          tag=f"two-block {kind} tail={tail}")
