@@ -2,9 +2,11 @@
 // the two encode drivers (cyclic-band register ring, generic CSR gather).
 //
 // Thread geometry shared by the scale pass and the encode+quantize+pack pass: a wave covers
-// one block of 256 consecutive coordinates, lane l owning the float4 at coordinates 4l..4l+3;
-// a workgroup is four waves.  Every lane walks over all workers for its four coordinates, so
-// the coded gradient f_i = sum_j a_ij g_j (Sec. II-A) only ever lives in registers.
+// one block of 256 consecutive coordinates, lane l owning the float4 at coordinates 4l..4l+3
+// (the max-abs scale pass may give a wave two neighbouring blocks at once); a workgroup is
+// four waves unless a kernel says otherwise.  Every lane walks over all workers for its
+// coordinates, so the coded gradient f_i = sum_j a_ij g_j (Sec. II-A) only ever lives in
+// registers.
 #pragma once
 
 #include <hip/hip_runtime.h>
