@@ -17,7 +17,10 @@
  *   - per-step calls validate their arguments synchronously, enqueue kernels on the given
  *     HIP stream (a hipStream_t passed as void*, NULL = the default stream) and return
  *     without waiting and without any host<->device copy: the small host arrays (bits, w,
- *     mask, code pointers) travel as kernel arguments;
+ *     mask, code pointers) travel as kernel arguments; they enqueue nothing but kernel launches
+ *     (no allocation, fill, copy or wait), so a caller may record them into a HIP graph: a
+ *     replay repeats the recorded call, seed and step counter included (not while the event
+ *     timing of agc_debug.h is switched on);
  *   - NaN or infinity in G is outside the contract (no check on the hot path);
  *   - a context's workspace and tables are shared by all its calls: calls on one context must be
  *     ordered (one stream, or events between streams); concurrent streams need one context each.

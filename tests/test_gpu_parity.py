@@ -449,3 +449,58 @@ def test_two_block_scale_pass_matches_oracle(kind, tail):
     out = run_hip(G, n, k, d, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_MAXABS, expect_path=path)
     compare_with_oracle(G_host, k, row_ptr, col, val, bits, w, mask, 77, 3, api.AGC_SCALE_MAXABS, out,
                           tag=f"two-block {kind} tail={tail}")
+
+
+# ---------------------------------------------------------------------------------------------
+# The hot calls enqueue kernel launches only, so a caller may record them into a HIP graph.  A
+# replay repeats the recorded step (same seed and step counter): every replay must reproduce the
+# eager result bit for bit, with eager work and synchronisations between the replays.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("unfused,scale_mode", [(False, api.AGC_SCALE_MAXABS), (True, api.AGC_SCALE_MAXABS),
+                                                (False, api.AGC_SCALE_L2)])
+def test_step_recorded_in_a_hip_graph_replays_the_eager_result(unfused, scale_mode):
+    import torch
+    rng = np.random.default_rng(909)
+    n = k = 8
+    d = 70001
+    row_ptr, col, val = cyclic_csr(rng, n, 3)
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = np.array([1, 0, 1, 1, 1, 0, 1, 1], dtype=np.uint8)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, unfused_step=unfused)
+    try:
+        ctx.agc_set_code(row_ptr, col, val)
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        ctx.agc_step(G, bits, w, mask, 5, 11, codes, scales, ghat)
+        torch.cuda.synchronize()
+        want = [c.clone() for c in codes], scales.clone(), ghat.clone()
+        # the eager result is the oracle's
+        compare_with_oracle(G_host, k, row_ptr, col, val, bits, w, mask, 5, 11, scale_mode,
+                            ([c.cpu().numpy() for c in codes], scales.cpu().numpy(), ghat.cpu().numpy()), tag="eager")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):      # one untimed run on the capture stream first
+            ctx.agc_step(G, bits, w, mask, 5, 11, codes, scales, ghat)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.agc_step(G, bits, w, mask, 5, 11, codes, scales, ghat)
+        for replay in range(3):
+            for c in codes:
+                c.fill_(0x5A)
+            scales.fill_(-1.0)
+            ghat.fill_(float("nan"))
+            ctx.agc_step(G, bits, w, mask, 6, 12 + replay, codes, scales, ghat)   # eager work in between, other draws
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for i in range(n):
+                assert torch.equal(codes[i], want[0][i]), (replay, i)
+            assert torch.equal(scales.view(torch.int32), want[1].view(torch.int32)), replay
+            assert torch.equal(ghat.view(torch.int32), want[2].view(torch.int32)), replay
+        del graph
+    finally:
+        ctx.close()
