@@ -103,11 +103,14 @@ constexpr int64_t kTwoBlockMin = 2 * 2 * 256 * 4 * 5;
 // of the tree), which keeps the result independent of how the waves were scheduled.
 // Max-abs scale: the maximum is exact and order-free.  A wave takes V neighbouring blocks (V = 2:
 // both at once through the two-block register ring when they lie wholly inside the vector and the
-// code has a ring driver, else one after the other), folds the n maxima into one of kMaxSlots
-// rows of a small array ([slot][worker]) with one integer atomic-max instruction (bit patterns of
-// non-negative floats order like the floats) and leaves; nothing waits, and the pass writes no
-// partial results to memory (stores mixed into the read stream cost far more than their bytes on
-// this memory system).  The finalize kernel reads the rows and hands them back zeroed.
+// code has a ring driver, else one after the other) and folds its n maxima into the workgroup's
+// LDS array with LDS atomics; the last wave of the workgroup to finish folds that array into one
+// of kMaxSlots rows of a small array in memory ([slot][worker]) with one integer atomic-max
+// instruction (bit patterns of non-negative floats order like the floats).  No wave waits for
+// another, and the pass writes no partial results to memory (stores mixed into the read stream
+// cost far more than their bytes on this memory system; even the atomics, performed in memory,
+// cost 22 us at one per wave and worker).  The finalize kernel reads the rows and hands them back
+// zeroed.
 template <int S, int MODE, int WAVES, int V>
 __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __restrict__ G,
                                                               const int* __restrict__ row_ptr,
@@ -130,26 +133,48 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
     double* accd = lds_acc[wave];
     uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
     if (MODE == 1) {
-        if (base >= a.d) return;
-        uint32_t* dst = a.part_max + (blk & (kMaxSlots - 1)) * a.n;
+        // the workgroup's running maxima and the count of waves that have delivered theirs
+        __shared__ uint32_t wg_max[kMaxWorkers];
+        __shared__ uint32_t wg_done;
+        for (int i = threadIdx.x; i < a.n; i += kWave * WAVES) wg_max[i] = 0u;
+        if (threadIdx.x == 0) wg_done = 0u;
+        __syncthreads();  // the only barrier: at the start, where no wave has anything to wait for
         EpiMaxAbs epi{accu, lane};
         auto fold = [&]() {  // accu[i] was written by this wave's lane 0
             for (int i = lane; i < a.n; i += kWave)
-                (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                (void)__hip_atomic_fetch_max(wg_max + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         };
-        if (V == 2 && S != 0 && base + 2 * kBlockCoords <= a.d) {
-            const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in both blocks
-            if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, val, lc, epi);
-            else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, B, lc, epi);
-            fold();
-        } else {
-            for (int u = 0; u < V; ++u) {
-                const int64_t b = base + (int64_t)u * kBlockCoords;
-                if (b < a.d) {
-                    const LaneCoords lc = lane_coords(b, lane, a.d);
-                    encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
-                    fold();
+        if (base < a.d) {
+            if (V == 2 && S != 0 && base + 2 * kBlockCoords <= a.d) {
+                const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in both blocks
+                if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, val, lc, epi);
+                else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, B, lc, epi);
+                fold();
+            } else {
+                for (int u = 0; u < V; ++u) {
+                    const int64_t b = base + (int64_t)u * kBlockCoords;
+                    if (b < a.d) {
+                        const LaneCoords lc = lane_coords(b, lane, a.d);
+                        encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
+                        fold();
+                    }
                 }
+            }
+        }
+        // Nobody waits for anybody: a wave that is done makes sure its maxima have reached wg_max
+        // (release fence: the wave's LDS operations have completed) and adds itself to the count;
+        // the wave that finds itself last hands the workgroup's maxima to the slot array - one
+        // memory-side atomic per worker and workgroup instead of one per wave.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        uint32_t before = 0u;
+        if (lane == 0) before = __hip_atomic_fetch_add(&wg_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        before = (uint32_t)__builtin_amdgcn_readfirstlane((int)before);
+        if (before == (uint32_t)(WAVES - 1)) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            uint32_t* dst = a.part_max + ((int64_t)blockIdx.x & (kMaxSlots - 1)) * a.n;
+            for (int i = lane; i < a.n; i += kWave) {
+                const uint32_t m = __hip_atomic_load(wg_max + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (m != 0u) (void)__hip_atomic_fetch_max(dst + i, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         return;
