@@ -199,41 +199,57 @@ __device__ __forceinline__ float4 fma4(float a, const float4& g, const float4& c
 }
 
 // What a lane holds of one row of G while it streams through a register ring: its float4 of one
-// block (float4 itself), or its float4s of two neighbouring blocks (Row2; the wave then covers 512
-// consecutive coordinates and issues two loads per row, 1 KiB apart).  The two-block form halves
-// the number of row walks and of per-worker reductions; it is used where registers allow it (the
-// max-abs scale pass).  Both forms perform the same arithmetic on every coordinate.
-struct Row2 {
-    float4 a, b;
+// block (float4 itself), or its float4s of V neighbouring blocks (RowN<V>; the wave then covers
+// 256 V consecutive coordinates and issues V loads per row, 1 KiB apart).  The multi-block form
+// divides the number of row walks and of per-worker reductions by V; it is used where registers
+// allow it (the max-abs scale pass).  All forms perform the same arithmetic on every coordinate.
+template <int V>
+struct RowN {
+    float4 v[V];
 };
-__device__ __forceinline__ Row2 mul4(float c, const Row2& g) { return Row2{mul4(c, g.a), mul4(c, g.b)}; }
-__device__ __forceinline__ Row2 fma4(float c, const Row2& g, const Row2& f)
+typedef RowN<2> Row2;
+template <int V>
+__device__ __forceinline__ RowN<V> mul4(float c, const RowN<V>& g)
 {
-    return Row2{fma4(c, g.a, f.a), fma4(c, g.b, f.b)};
+    RowN<V> r;
+#pragma unroll
+    for (int t = 0; t < V; ++t) r.v[t] = mul4(c, g.v[t]);
+    return r;
+}
+template <int V>
+__device__ __forceinline__ RowN<V> fma4(float c, const RowN<V>& g, const RowN<V>& f)
+{
+    RowN<V> r;
+#pragma unroll
+    for (int t = 0; t < V; ++t) r.v[t] = fma4(c, g.v[t], f.v[t]);
+    return r;
 }
 
+// Row -> number of blocks
 template <class Row>
-__device__ __forceinline__ Row zero_row();
-template <>
-__device__ __forceinline__ float4 zero_row<float4>() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-template <>
-__device__ __forceinline__ Row2 zero_row<Row2>()
+struct RowBlocks {
+    static constexpr int value = sizeof(Row) / sizeof(float4);
+};
+
+template <class Row>
+__device__ __forceinline__ Row zero_row()
 {
-    return Row2{make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+    Row r;
+    float4* p = reinterpret_cast<float4*>(&r);
+#pragma unroll
+    for (int t = 0; t < RowBlocks<Row>::value; ++t) p[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return r;
 }
 
 // streaming load of a lane's part of a row whose blocks lie wholly inside the vector
 template <class Row>
-__device__ __forceinline__ Row load_row(const float* __restrict__ row, const LaneCoords& lc);
-template <>
-__device__ __forceinline__ float4 load_row<float4>(const float* __restrict__ row, const LaneCoords& lc)
+__device__ __forceinline__ Row load_row(const float* __restrict__ row, const LaneCoords& lc)
 {
-    return load_row4<false, true>(row, lc);
-}
-template <>
-__device__ __forceinline__ Row2 load_row<Row2>(const float* __restrict__ row, const LaneCoords& lc)
-{
-    return Row2{load_row4<false, true>(row, lc), load_row4<false, true>(row + kBlockCoords, lc)};
+    Row r;
+    float4* p = reinterpret_cast<float4*>(&r);
+#pragma unroll
+    for (int t = 0; t < RowBlocks<Row>::value; ++t) p[t] = load_row4<false, true>(row + t * kBlockCoords, lc);
+    return r;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -266,9 +282,13 @@ __device__ __forceinline__ float4 sel4(bool c, const float4 a, const float4 b)
 {
     return make_float4(c ? a.x : b.x, c ? a.y : b.y, c ? a.z : b.z, c ? a.w : b.w);
 }
-__device__ __forceinline__ Row2 sel4(bool c, const Row2& a, const Row2& b)
+template <int V>
+__device__ __forceinline__ RowN<V> sel4(bool c, const RowN<V>& a, const RowN<V>& b)
 {
-    return Row2{sel4(c, a.a, b.a), sel4(c, a.b, b.b)};
+    RowN<V> r;
+#pragma unroll
+    for (int t = 0; t < V; ++t) r.v[t] = sel4(c, a.v[t], b.v[t]);
+    return r;
 }
 
 // stash helpers with compile-time indices (so the stash stays in registers)

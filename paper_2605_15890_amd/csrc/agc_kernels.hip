@@ -57,10 +57,13 @@ struct EpiMaxAbs {
         const uint32_t m = wave_max_nonneg_bits(max_abs4(f));
         if (lane == 0) acc[i] = m;
     }
-    template <bool EVEN>
-    __device__ __forceinline__ void worker(int i, const Row2& f)  // two blocks, one reduction
+    template <bool EVEN, int V>
+    __device__ __forceinline__ void worker(int i, const RowN<V>& f)  // V blocks, one reduction
     {
-        const uint32_t m = wave_max_nonneg_bits(fmaxf(max_abs4(f.a), max_abs4(f.b)));
+        float a = max_abs4(f.v[0]);
+#pragma unroll
+        for (int t = 1; t < V; ++t) a = fmaxf(a, max_abs4(f.v[t]));
+        const uint32_t m = wave_max_nonneg_bits(a);
         if (lane == 0) acc[i] = m;
     }
     template <class Row>
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
                                                               ScaleArgs a)
 {
     static_assert(MODE == 1 || (WAVES == kSegBlocks && V == 1), "the norm's tree fixes four blocks per workgroup");
-    static_assert(V == 1 || V == 2, "one or two blocks per wave");
+    static_assert(V == 1 || V == 2 || V == 4, "one, two or four blocks per wave");
     __shared__ double lds_acc[WAVES][kMaxWorkers];
     // the wave index is the same for all lanes: tell the compiler, so that everything derived
     // from it (block base, pointers) lives in scalar registers
@@ -145,10 +148,10 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
                 (void)__hip_atomic_fetch_max(wg_max + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         };
         if (base < a.d) {
-            if (V == 2 && S != 0 && base + 2 * kBlockCoords <= a.d) {
-                const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in both blocks
-                if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, val, lc, epi);
-                else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, Row2>(G + base, a.ldg, a.k, B, lc, epi);
+            if (V > 1 && S != 0 && base + V * kBlockCoords <= a.d) {
+                const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in all V blocks
+                if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, RowN<V>>(G + base, a.ldg, a.k, val, lc, epi);
+                else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, RowN<V>>(G + base, a.ldg, a.k, B, lc, epi);
                 fold();
             } else {
                 for (int u = 0; u < V; ++u) {
@@ -191,7 +194,9 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
         double sum = 0.0;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) sum = sum + lds_acc[w][i];
-        a.part_sq[seg * (int64_t)a.n + i] = sum;  // [segment][worker]: one coalesced row per workgroup
+        // [segment][worker]: one coalesced row per workgroup, non-temporal (a plain store costs the
+        // pass 30 us more: the dirty lines leave the cache in the middle of the read stream)
+        __builtin_nontemporal_store(sum, a.part_sq + seg * (int64_t)a.n + i);
     }
 }
 
@@ -235,7 +240,7 @@ static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const
         // two blocks per wave where a ring driver serves the code and the vector is long enough
         // to fill the chip with half as many waves
         const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
-        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE == 2 && nblocks >= kTwoBlockMin) launch_scale_max<S, 2>(G, code, a, stream);
+        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE > 1 && nblocks >= kTwoBlockMin) launch_scale_max<S, AGC_SCALE_BLOCKS_PER_WAVE>(G, code, a, stream);
         else launch_scale_max<S, 1>(G, code, a, stream);
     }
     return hipGetLastError();
