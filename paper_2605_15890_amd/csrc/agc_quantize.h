@@ -53,6 +53,22 @@ constexpr int kBufferRsrcFlags = 0x00020000;
 #endif
 constexpr int kPayloadStorePolicy = AGC_PAYLOAD_POLICY;
 
+// cache-policy operand of the store of the fused estimate: sc1 alone (written through).  Next to
+// the payload stores: plain 1.41-1.42 ms, non-temporal 1.43, sc1 1.40-1.41.
+constexpr int kEstimateStorePolicy = 16;
+
+// buffer descriptor over `bytes` bytes at a wave-uniform address (the hardware drops accesses at
+// offsets >= bytes).  The two halves of the address go through readfirstlane as unsigned words:
+// the builtin returns a signed int, and a sign-extended low word would corrupt the high one.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_buffer(const void* p, int bytes)
+{
+    const uint64_t bits = (uint64_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)bits);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(bits >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((char*)(((uint64_t)hi << 32) | (uint64_t)lo), 0,
+                                             __builtin_amdgcn_readfirstlane(bytes), kBufferRsrcFlags);
+}
+
 // One rounding decision (Sec. II-B): T is the grid position scaled by 2^16; the cell is
 // T >> 16, the low 16 bits are the first 16 bits of the round-up probability, compared with
 // the 16-bit primary draw; equality is a tie, resolved later by a secondary draw.
@@ -137,12 +153,8 @@ struct EpiQuant {
             const WorkerQ w = load_uniform(wq + j);
             const int b = (int)w.bits;
             const int np = 2 * kQuantWaves * b;  // pieces of this worker in the area
-            const uint64_t dst_bits = (uint64_t)w.codes + (uint64_t)wg * (uint64_t)(32 * kQuantWaves * b);
-            const uint32_t dst_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)dst_bits);
-            const uint32_t dst_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(dst_bits >> 32));
-            char* dst = (char*)(((uint64_t)dst_hi << 32) | (uint64_t)dst_lo);
-            const int valid_bytes = __builtin_amdgcn_readfirstlane(16 * b * wg_groups);
-            const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, valid_bytes, kBufferRsrcFlags);
+            const __amdgpu_buffer_rsrc_t rsrc = uniform_buffer(
+                (const char*)w.codes + (uint64_t)wg * (uint64_t)(32 * kQuantWaves * b), 16 * b * wg_groups);
             const uint32_t first = w.stage_piece * (uint32_t)(kQuantWaves / 4);  // the table counts for four waves
             for (int off = 0; off < np; off += kWave) {
                 const int piece = off + lane;
@@ -409,7 +421,10 @@ __global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S
     if constexpr (FUSE) {
         float* dst = a.ghat + base + 4 * lane;
         if (lc.nvalid == 4) {
-            *reinterpret_cast<float4*>(dst) = make_float4(epi.acc[0], epi.acc[1], epi.acc[2], epi.acc[3]);
+            const __amdgpu_buffer_rsrc_t rs = uniform_buffer(a.ghat + base, 4 * kBlockCoords);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(epi.acc[0]), __float_as_uint(epi.acc[1]),
+                                                           __float_as_uint(epi.acc[2]), __float_as_uint(epi.acc[3])},
+                                                   rs, 16 * lane, 0, kEstimateStorePolicy);
         } else {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
