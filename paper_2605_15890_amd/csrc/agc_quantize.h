@@ -55,7 +55,10 @@ constexpr int kPayloadStorePolicy = AGC_PAYLOAD_POLICY;
 
 // cache-policy operand of the store of the fused estimate: sc1 alone (written through).  Next to
 // the payload stores: plain 1.41-1.42 ms, non-temporal 1.43, sc1 1.40-1.41.
-constexpr int kEstimateStorePolicy = 16;
+#ifndef AGC_ESTIMATE_POLICY
+#define AGC_ESTIMATE_POLICY 16
+#endif
+constexpr int kEstimateStorePolicy = AGC_ESTIMATE_POLICY;
 
 // buffer descriptor over `bytes` bytes at a wave-uniform address (the hardware drops accesses at
 // offsets >= bytes).  The two halves of the address go through readfirstlane as unsigned words:
