@@ -504,3 +504,37 @@ def test_step_recorded_in_a_hip_graph_replays_the_eager_result(unfused, scale_mo
         del graph
     finally:
         ctx.close()
+
+
+def test_two_block_scale_pass_with_the_maximum_worker_count():
+    """n = 256 workers over k = 8 partitions (interval code, window driver) at a size where the
+    max-abs scale pass takes two blocks per wave: every worker's scale against the oracle, and the
+    codes of a few workers in a window that straddles the last whole pair of blocks."""
+    import torch
+    rng = np.random.default_rng(4242)
+    n, k = api.AGC_MAX_WORKERS, 8
+    d = TWO_BLOCK_MIN * 256 + 300
+    row_ptr, col, val = monotone_csr(rng, n, k, 4)
+    G_host = (rng.standard_normal((k, d)) * 0.01).astype(np.float32)
+    spots = [300, d - 1, (d - 1) // 256 * 256 - 3, (d // 512 - 1) * 512 + 17, 512 * 4097 + 511, 7, 511, d - 301]
+    for j in range(k):
+        G_host[j, spots[j]] = np.float32(2.0 + j)
+    bits = np.full(n, 2, dtype=np.uint8)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS)
+    try:
+        ctx.agc_set_code(row_ptr, col, val)
+        assert ctx.agc_code_path() > 100
+        codes, scales, _ = ctx.alloc_outputs(bits)
+        ctx.agc_encode_quantize(G, bits, 31, 2, codes, scales)
+        torch.cuda.synchronize()
+        csr = O.Csr(row_ptr, col, val, k)
+        o_scales = O.scales(G_host, csr, api.AGC_SCALE_MAXABS)
+        assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
+        m0, m1 = (d // 512 - 1) * 512 - 256, d
+        for i in (0, 1, 100, n - 1):
+            want = O.codes_range(G_host, csr, i, 2, o_scales[i], 31, 2, m0, m1)
+            got = O.unpack(codes[i].cpu().numpy(), d, 2)[m0:m1]
+            assert np.array_equal(got, want), i
+    finally:
+        ctx.close()
