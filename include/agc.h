@@ -91,8 +91,9 @@ typedef struct {
  * Context
  * ------------------------------------------------------------------------------------ */
 /* Creates a context for n workers, k partitions, d coordinates on the current device and
- * allocates its workspace (scale partials: 4 bytes * n * ceil(d/256) for the max-abs scale,
- * 8 bytes * n * ceil(d/1024) for the Euclidean one; a few n-entry tables).
+ * allocates its workspace (scale partials: 4 bytes * 256 * n for the max-abs scale, whatever d is;
+ * 8 bytes * n * ceil(d/1024) for the Euclidean one; none with bucket-wise scales; a few n-entry
+ * tables).
  * opts may be NULL (AGC_SCALE_MAXABS, no 1-bit).  Limits: 1 <= n <= AGC_MAX_WORKERS,
  * 1 <= k <= 65536, 1 <= d <= 2^33. */
 agc_status agc_create(agc_ctx **out, int n_workers, int k_parts, int64_t d, const agc_opts *opts);
