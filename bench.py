@@ -274,6 +274,8 @@ def measured_ceilings(api, G, k, d, scratch):
     ms = timed(lambda: api.agc_debug_stream_rows(G, 0, scratch))
     out["pattern_read_ms"] = round(ms, 4)
     out["pattern_read_GBps"] = round(g_bytes / (ms * 1e-3) / 1e9, 1)
+    ms = timed(lambda: api.agc_debug_stream_rows(G, 0, scratch, blocks_per_wave=2))
+    out["pattern_read_two_block_ms"] = round(ms, 4)
     piece = 96
     w_bytes = float(k) * (d // 256) * piece
     ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=False))
@@ -281,7 +283,7 @@ def measured_ceilings(api, G, k, d, scratch):
     ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=True))
     out["pattern_read_write_ms"] = round(ms, 4)
     out["pattern_read_write_GBps"] = round((g_bytes + w_bytes) / (ms * 1e-3) / 1e9, 1)
-    out["pattern_note"] = (f"bare row walk over G ({g_bytes / 1e9:.2f} GB); with writes: plus {w_bytes / 1e9:.3f} GB "
+    out["pattern_note"] = (f"bare row walk over G ({g_bytes / 1e9:.2f} GB), one block per wave or two (the max-abs scale pass's form); with writes: plus {w_bytes / 1e9:.3f} GB "
                            f"in {piece}-byte pieces per block to {k} streams, stored per wave after every row "
                            f"(per_wave) or per workgroup as {4 * piece}-byte lines after a barrier (the quantize pass's form)")
     return out

@@ -51,13 +51,16 @@ agc_status agc_calibration_copy(void *dst_dev, const void *src_dev, int64_t byte
  *   wg_flush != 0: a workgroup (four blocks) keeps its pieces until it has walked all rows and then,
  *                  after one barrier, writes 4 * piece_bytes contiguous bytes per row (what the
  *                  quantize pass does through its LDS staging area).
+ *   blocks_per_wave: 1, or 2 with piece_bytes == 0: a wave walks two neighbouring blocks at once
+ *                  (two loads per row, 1 KiB apart, two rows in flight), the form of the max-abs
+ *                  scale pass on long vectors; only whole pairs of blocks are read then.
  * Only whole blocks are touched (floor(d/256) of them).  What this kernel reaches is what the
  * memory system delivers for that traffic, whatever the arithmetic on top of it.
  *   G_dev    device, k x d binary32, row stride ldg (multiple of 4), 16-byte aligned; read-only
  *   out_dev  device, 16-byte aligned, at least max(16, k * floor(d/256) * piece_bytes) bytes
  */
 agc_status agc_debug_stream_rows(const float *G_dev, int64_t ldg, int k, int64_t d, int piece_bytes,
-                                 int wg_flush, void *out_dev, void *hip_stream);
+                                 int wg_flush, int blocks_per_wave, void *out_dev, void *hip_stream);
 
 #ifdef __cplusplus
 }

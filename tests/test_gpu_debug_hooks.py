@@ -42,7 +42,11 @@ def test_stream_rows_touches_exactly_its_output_region(k, d, piece):
             per = piece // 4                                           # floats per piece
             want = np.stack([G_host[j, :nblocks * 256].reshape(nblocks, 256)[:, :per].reshape(-1) for j in range(k)])
             assert np.array_equal(o[:k * nblocks * per].reshape(k, nblocks * per), want)
-    out = torch.full((1024,), canary, dtype=torch.float32, device="cuda")
-    api.agc_debug_stream_rows(G, 0, out)
-    torch.cuda.synchronize()
-    assert bool((out == canary).all())
+    for per_wave in (1, 2):
+        out = torch.full((1024,), canary, dtype=torch.float32, device="cuda")
+        api.agc_debug_stream_rows(G, 0, out, blocks_per_wave=per_wave)
+        torch.cuda.synchronize()
+        assert bool((out == canary).all())
+    with pytest.raises(api.AgcError):     # the two-block walk is a reads-only form
+        api.agc_debug_stream_rows(G, piece, torch.empty(region + 1024, dtype=torch.float32, device="cuda"),
+                                  blocks_per_wave=2)
