@@ -538,3 +538,39 @@ def test_two_block_scale_pass_with_the_maximum_worker_count():
             assert np.array_equal(got, want), i
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("kind", ["cyclic1", "cyclic2", "cyclic4", "cyclic5", "cyclic8", "window2", "window8"])
+def test_two_block_scale_pass_every_driver_width(kind):
+    """Scales of the two-block max-abs pass for every width of the ring and window drivers that the
+    other two-block tests do not reach (they take widths 3 and 4), against the oracle."""
+    import torch
+    width = int(kind[6:])
+    rng = np.random.default_rng(5200 + width + (100 if kind.startswith("window") else 0))
+    d = TWO_BLOCK_MIN * 256 + 300
+    if kind.startswith("cyclic"):
+        n = k = 9
+        row_ptr, col, val = cyclic_csr(rng, n, width)
+        path = width
+    else:
+        n, k = 11, 9
+        row_ptr, col, val = monotone_csr(rng, n, k, width)
+        longest = int(np.max(np.diff(row_ptr)))
+        path = 100 + (2 if longest <= 2 else 4 if longest <= 4 else 8)
+    G_host = (rng.standard_normal((k, d)) * 0.01).astype(np.float32)
+    spots = [300, d - 1, (d - 1) // 256 * 256 - 3, (d // 512 - 1) * 512 + 17, 512 * 4097 + 511, 7, 511, d - 301, 256]
+    for j in range(k):
+        G_host[j, spots[j]] = np.float32(2.0 + j)
+    bits = np.full(n, 2, dtype=np.uint8)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS)
+    try:
+        ctx.agc_set_code(row_ptr, col, val)
+        assert ctx.agc_code_path() == path
+        codes, scales, _ = ctx.alloc_outputs(bits)
+        ctx.agc_encode_quantize(G, bits, 31, 2, codes, scales)
+        torch.cuda.synchronize()
+        o_scales = O.scales(G_host, O.Csr(row_ptr, col, val, k), api.AGC_SCALE_MAXABS)
+        assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
+    finally:
+        ctx.close()
