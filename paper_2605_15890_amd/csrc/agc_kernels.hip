@@ -222,7 +222,9 @@ hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stre
 template <int S, int V>
 static void launch_scale_max(const float* G, const CodeDev& code, const ScaleArgs& a, hipStream_t stream)
 {
-    constexpr int W = AGC_SCALE_WAVES;
+    // the widest two-block rings leave room for three waves per SIMD: workgroups of four waves
+    // then fill a compute unit (three of them), workgroups of eight would not (one)
+    constexpr int W = (V > 1 && S >= 7) ? 4 : AGC_SCALE_WAVES;
     const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
     const int64_t per_wg = (int64_t)W * V;
     hipLaunchKernelGGL((k_scale_pass<S, 1, W, V>), dim3((unsigned)((nblocks + per_wg - 1) / per_wg)), dim3(kWave * W),
