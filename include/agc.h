@@ -56,6 +56,7 @@ extern "C" {
 
 #define AGC_MAX_WORKERS 256   /* n <= 256: per-worker arguments travel in the kernel argument block */
 #define AGC_MAX_BITS 16
+#define AGC_MAX_LAYERS 256    /* layer-wise scales: at most this many layers */
 
 typedef struct agc_ctx agc_ctx; /* opaque; owns device workspace and a copy of B */
 
@@ -111,6 +112,22 @@ void agc_destroy(agc_ctx *ctx);
  * identical bits (agc_code_path tells which one a context runs). */
 agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col, const float *val);
 
+/* Layer-wise scales (Sec. II-B: the quantizer "at layer-wise or bucket-wise granularity"): the d
+ * coordinates are cut into n_layers consecutive layers, layer l = [layer_end[l-1], layer_end[l])
+ * with layer_end[-1] = 0, and every worker gets one max-abs scale per layer,
+ * scale_il = max over the layer of |f_i[m]|.  Everything else is the per-vector arithmetic with
+ * the layer's scale in place of the vector's: inv16_il = (float)(L_i * 2^16 / scale_il), decode
+ * weight (float)(((double)w_i * scale_il) / L_i); draws and payload layout do not change.  With
+ * layers set, scales_dev of the per-step calls holds n x n_layers floats, [worker][layer]
+ * (agc_scales_per_worker), and agc_encode_quantize, agc_decode, agc_decode2 and agc_step (both
+ * forms) work on them; the worker side still reads G twice.
+ *   layer_end  host, n_layers ends, strictly ascending, all but the last multiples of 256 (a
+ *              256-coordinate block lies in one layer), the last equal to d
+ * 1 <= n_layers <= AGC_MAX_LAYERS; n_layers == 0 returns to one scale per vector.  Needs a context
+ * with AGC_SCALE_MAXABS and bucket == 0 (AGC_EINVAL otherwise).  Synchronous (waits for the device,
+ * replaces small tables); not available in agc_decode_noalloc, which has no context. */
+agc_status agc_set_layers(agc_ctx *ctx, int n_layers, const int64_t *layer_end);
+
 /* 0 = generic gather path; 1..8 = cyclic-band path with replication s; 102, 104, 108 = monotone-
  * interval path (every row a run of at most 2, 4, 8 consecutive ascending columns whose ends never
  * decrease from one worker to the next - the shape agc_build_code produces); < 0 = no code set.
@@ -121,7 +138,7 @@ int agc_code_path(const agc_ctx *ctx);
  * the scale plus d codes of b bits; the padding is this library's). */
 int64_t agc_code_bytes(int64_t d, int bits);
 
-/* Scales per worker in scales_dev: 1, or ceil(d/256) with bucket-wise scales. */
+/* Scales per worker in scales_dev: 1, ceil(d/256) with bucket-wise scales, n_layers with layer-wise scales. */
 int64_t agc_scales_per_worker(const agc_ctx *ctx);
 
 const char *agc_last_error(const agc_ctx *ctx);

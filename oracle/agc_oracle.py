@@ -437,3 +437,53 @@ def step(G, csr, bits, w, mask, seed, step_, scale_mode):
                           int(step_), int(scale_mode), sp, sc_out.ctypes.data_as(_f32p),
                           ghat.ctypes.data_as(_f32p))
     return streams, sc_out, ghat
+
+
+# ------------------------------------------------------------------ layer-wise scales
+# Sec. II-B applies the quantizer "at layer-wise or bucket-wise granularity": the coded vector is
+# cut into consecutive layers and each layer is quantized as a vector of its own, with its own
+# scale; the draws stay those of the coordinate's place in the whole vector.  Written out with
+# the per-vector routines above: nothing here has arithmetic of its own.
+def layer_ranges(ends, d):
+    ends = [int(e) for e in ends]
+    assert ends and ends[-1] == int(d) and all(b > a for a, b in zip([0] + ends[:-1], ends))
+    return list(zip([0] + ends[:-1], ends))
+
+
+def scales_layers(G, csr, ends):
+    """(n, n_layers) float32: largest magnitude of f_i inside every layer."""
+    G, _ = _f32(G)
+    ranges = layer_ranges(ends, G.shape[1])
+    out = np.zeros((csr.n, len(ranges)), dtype=np.float32)
+    for i in range(csr.n):
+        for l, (m0, m1) in enumerate(ranges):
+            out[i, l] = scale_maxabs(encode(G, csr, i, m0, m1))
+    return out
+
+
+def encode_quantize_layers(G, csr, bits, seed, step_, ends, scales_in=None):
+    """Streams and (n, n_layers) scales: layer l of worker i is quantized with scale [i, l]."""
+    G, _ = _f32(G)
+    d = G.shape[1]
+    ranges = layer_ranges(ends, d)
+    sc = scales_layers(G, csr, ends) if scales_in is None else np.asarray(scales_in, dtype=np.float32)
+    streams = []
+    for i in range(csr.n):
+        codes = np.concatenate([codes_range(G, csr, i, int(bits[i]), sc[i, l], seed, step_, m0, m1)
+                                for l, (m0, m1) in enumerate(ranges)])
+        streams.append(pack(codes, int(bits[i])))
+    return streams, sc
+
+
+def decode_layers(streams, scales, bits, w, mask, d, ends):
+    """scales: (n, n_layers).  Every layer is decoded with its own column of scales."""
+    scales = np.asarray(scales, dtype=np.float32)
+    return np.concatenate([decode(streams, np.ascontiguousarray(scales[:, l]), bits, w, mask, d, m0, m1)
+                           for l, (m0, m1) in enumerate(layer_ranges(ends, d))])
+
+
+def step_layers(G, csr, bits, w, mask, seed, step_, ends):
+    """One whole pass with layer-wise max-abs scales.  Returns (streams, scales (n, n_layers), ghat)."""
+    G, _ = _f32(G)
+    streams, sc = encode_quantize_layers(G, csr, bits, seed, step_, ends)
+    return streams, sc, decode_layers(streams, sc, bits, w, mask, G.shape[1], ends)

@@ -15,13 +15,13 @@ LIB_PATH = os.path.join(_HERE, "libagc.so")
 AGC_OK = 0
 AGC_EINVAL, AGC_ESHAPE, AGC_EBITS, AGC_EALIGN, AGC_ENOMEM, AGC_EHIP, AGC_ESTATE = -1, -2, -3, -4, -5, -6, -7
 AGC_SCALE_L2, AGC_SCALE_MAXABS = 0, 1
-AGC_MAX_WORKERS, AGC_MAX_BITS, AGC_NUM_KERNELS = 256, 16, 4
+AGC_MAX_WORKERS, AGC_MAX_BITS, AGC_NUM_KERNELS, AGC_MAX_LAYERS = 256, 16, 4, 256
 KERNEL_NAMES = ("scale_pass", "scale_finalize", "quantize", "decode")
 
 EXPORTS = [
     "agc_create", "agc_destroy", "agc_set_code", "agc_code_path", "agc_code_bytes", "agc_last_error",
     "agc_encode_quantize", "agc_decode", "agc_step", "agc_profile_enable", "agc_profile_read",
-    "agc_scales_per_worker", "agc_decode2", "agc_decode_noalloc", "agc_adam_update", "agc_second_moment_decoder",
+    "agc_scales_per_worker", "agc_set_layers", "agc_decode2", "agc_decode_noalloc", "agc_adam_update", "agc_second_moment_decoder",
     "agc_calibration_copy", "agc_debug_stream_rows", "agc_ls_workspace_floats", "agc_ls_partial_gradients", "agc_gd_update",
     "agc_phi_coef_balanced", "agc_alloc_bits", "agc_alloc_bits_dp", "agc_alloc_objective",
     "agc_build_code", "agc_build_cyclic_code", "agc_build_cyclic_code_opt", "agc_check_unbiased",
@@ -80,6 +80,8 @@ def load():
     L.agc_decode.restype = C.c_int
     L.agc_scales_per_worker.argtypes = [_vp]
     L.agc_scales_per_worker.restype = C.c_int64
+    L.agc_set_layers.argtypes = [_vp, C.c_int, C.POINTER(C.c_int64)]
+    L.agc_set_layers.restype = C.c_int
     L.agc_decode2.argtypes = [_vp, C.POINTER(_vp), _vp, _u8p, _f32p, _f32p, _u8p, _vp, _vp, _vp]
     L.agc_decode2.restype = C.c_int
     L.agc_decode_noalloc.argtypes = [C.c_int, C.c_int64, C.c_int, C.POINTER(_vp), _vp, _u8p, _f32p, _u8p, _vp, _vp]
@@ -289,6 +291,13 @@ class Context:
         row_ptr, col, val = _np(row_ptr, np.int32), _np(col, np.int32), _np(val, np.float32)
         self._check(self.lib.agc_set_code(self.h, _ptr(row_ptr, _i32p), _ptr(col, _i32p), _ptr(val, _f32p)))
 
+    def agc_set_layers(self, layer_end):
+        """Layer-wise max-abs scales: layer_end = ascending ends of the layers (all but the last multiples
+        of 256, the last equal to d); an empty sequence returns to one scale per vector."""
+        ends = np.ascontiguousarray(np.asarray(layer_end, dtype=np.int64))
+        ptr = ends.ctypes.data_as(C.POINTER(C.c_int64)) if ends.size else None
+        self._check(self.lib.agc_set_layers(self.h, int(ends.size), ptr))
+
     def agc_code_path(self):
         return int(self.lib.agc_code_path(self.h))
 
@@ -301,7 +310,7 @@ class Context:
         bits = _np(bits, np.uint8)
         codes = [torch.empty(agc_code_bytes(self.d, int(b)), dtype=torch.uint8, device=device) for b in bits]
         per = self.agc_scales_per_worker()
-        scales = torch.empty((self.n, per) if self.bucket else self.n, dtype=torch.float32, device=device)
+        scales = torch.empty((self.n, per) if per > 1 or self.bucket else self.n, dtype=torch.float32, device=device)
         ghat = torch.empty(self.d, dtype=torch.float32, device=device)
         return codes, scales, ghat
 

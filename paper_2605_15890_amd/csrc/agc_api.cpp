@@ -72,6 +72,17 @@ hipError_t dev_alloc(T** p, size_t count)
     return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
 }
 
+void free_layers(agc_ctx* c)
+{
+    if (c->ws.block_layer) (void)hipFree(const_cast<uint8_t*>(c->ws.block_layer));
+    if (c->ws.coef_layer) (void)hipFree(c->ws.coef_layer);
+    if (c->ws.coef2_layer) (void)hipFree(c->ws.coef2_layer);
+    c->ws.block_layer = nullptr;
+    c->ws.coef_layer = nullptr;
+    c->ws.coef2_layer = nullptr;
+    c->ws.n_layers = 0;
+}
+
 void free_code(agc_ctx* c)
 {
     if (c->d_row_ptr) (void)hipFree(c->d_row_ptr);
@@ -169,7 +180,8 @@ int64_t agc_code_bytes(int64_t d, int bits)
 int64_t agc_scales_per_worker(const agc_ctx* ctx)
 {
     if (!ctx) return 0;
-    return ctx->opts.bucket ? (ctx->d + 255) / 256 : 1;
+    if (ctx->opts.bucket) return (ctx->d + 255) / 256;
+    return ctx->ws.n_layers > 0 ? ctx->ws.n_layers : 1;
 }
 
 const char* agc_last_error(const agc_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
@@ -233,6 +245,7 @@ void agc_destroy(agc_ctx* c)
 {
     if (!c) return;
     free_code(c);
+    free_layers(c);
     if (c->ws.part_max) (void)hipFree(c->ws.part_max);
     if (c->ws.part_sq) (void)hipFree(c->ws.part_sq);
     if (c->ws.group_sq) (void)hipFree(c->ws.group_sq);
@@ -322,6 +335,66 @@ agc_status agc_set_code(agc_ctx* c, const int32_t* row_ptr, const int32_t* col, 
     c->nnz = nnz;
     c->band = band;
     c->has_code = true;
+    return AGC_OK;
+}
+
+agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
+{
+    if (!c) return AGC_EINVAL;
+    if (n_layers < 0 || n_layers > AGC_MAX_LAYERS)
+        return fail(c, AGC_ESHAPE, "n_layers must lie in 0.." + std::to_string(AGC_MAX_LAYERS));
+    // nothing of the old tables may still be in use by a kernel when they are replaced
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(c, e, "hipDeviceSynchronize");
+    if (n_layers == 0) {
+        free_layers(c);
+        return AGC_OK;
+    }
+    if (c->opts.bucket || c->opts.scale_mode != AGC_SCALE_MAXABS)
+        return fail(c, AGC_EINVAL, "layer-wise scales need AGC_SCALE_MAXABS and bucket == 0");
+    if (!layer_end) return fail(c, AGC_EINVAL, "layer_end is null");
+    int64_t prev = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int64_t end = layer_end[l];
+        if (end <= prev) return fail(c, AGC_ESHAPE, "layer ends must be positive and strictly ascending");
+        if (l + 1 < n_layers && (end & 255))
+            return fail(c, AGC_ESHAPE, "layer end " + std::to_string(end) + " is not a multiple of 256");
+        prev = end;
+    }
+    if (prev != c->d) return fail(c, AGC_ESHAPE, "the last layer must end at d");
+    const int64_t nblocks = (c->d + 255) / 256;
+    std::vector<uint8_t> layer_of((size_t)nblocks);
+    {
+        int l = 0;
+        for (int64_t blk = 0; blk < nblocks; ++blk) {
+            while (blk * 256 >= layer_end[l]) ++l;  // ends before the last are block boundaries
+            layer_of[(size_t)blk] = (uint8_t)l;
+        }
+    }
+    uint8_t* d_layer = nullptr;
+    agc::WorkerQ* d_wq = nullptr;
+    float *d_c1 = nullptr, *d_c2 = nullptr;
+    const size_t entries = (size_t)c->n * (size_t)n_layers;
+    e = dev_alloc(&d_layer, (size_t)nblocks);
+    if (e == hipSuccess) e = dev_alloc(&d_wq, entries);
+    if (e == hipSuccess) e = dev_alloc(&d_c1, entries);
+    if (e == hipSuccess) e = dev_alloc(&d_c2, entries);
+    if (e == hipSuccess) e = hipMemcpy(d_layer, layer_of.data(), (size_t)nblocks, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (d_layer) (void)hipFree(d_layer);
+        if (d_wq) (void)hipFree(d_wq);
+        if (d_c1) (void)hipFree(d_c1);
+        if (d_c2) (void)hipFree(d_c2);
+        return fail(c, e == hipErrorOutOfMemory ? AGC_ENOMEM : AGC_EHIP,
+                    std::string("layer tables: ") + hipGetErrorString(e));
+    }
+    free_layers(c);
+    if (c->ws.wq) (void)hipFree(c->ws.wq);
+    c->ws.wq = d_wq;  // one table per layer; a later return to one scale per vector uses the first
+    c->ws.block_layer = d_layer;
+    c->ws.coef_layer = d_c1;
+    c->ws.coef2_layer = d_c2;
+    c->ws.n_layers = n_layers;
     return AGC_OK;
 }
 

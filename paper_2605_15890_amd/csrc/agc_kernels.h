@@ -105,9 +105,17 @@ struct Workspace {
     float* coef2;         // [n]  second-track weights v_i * scale_i / L_i of the arrived workers
     const float** srow;   // [n]  bucket-wise scales: row of scales of every arrived worker
     int64_t nseg, ngroup, nsuper;
+    // layer-wise scales (n_layers > 0; max-abs only): the layer of every 256-coordinate block, and
+    // the decode weights w_i * scale_il / L_i (and v_i * ...) of the arrived workers, [layer][slot].
+    // wq then holds one table per layer, [layer][n].
+    const uint8_t* block_layer;  // [ceil(d/256)]
+    int n_layers;
+    float* coef_layer;    // [n_layers][n]
+    float* coef2_layer;   // [n_layers][n]
 };
 
 constexpr int kMaxSlots = 256;  // rows of the max-abs array; a block folds into row (block mod kMaxSlots)
+constexpr int kMaxLayers = kMaxSlots;  // with layer-wise scales row l of the array belongs to layer l
 
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];
@@ -140,7 +148,8 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              hipStream_t stream);
 // all rows of the max-abs slot array back to zero
 hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stream);
-// K1f: partials -> scales[n] and the per-worker table of the quantize pass.
+// K1f: partials -> scales[n] and the per-worker table of the quantize pass (with layer-wise scales:
+// scales[n][n_layers] and one table per layer).
 // sw.fuse != 0: the quantize pass that follows also forms the estimate (ghat) from the codes it
 // has just produced, in the same order and arithmetic as the decode kernel.
 hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,

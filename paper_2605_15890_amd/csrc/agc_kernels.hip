@@ -36,6 +36,7 @@ struct ScaleArgs {
     uint32_t* part_max;
     double* part_sq;
     const WindowRec* win;  // monotone-interval codes only
+    const uint8_t* block_layer;  // layer-wise scales only (max-abs): the layer of every block
 };
 
 // the same 32-bit word seen as device memory (store without address-space checks)
@@ -136,6 +137,24 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
     double* accd = lds_acc[wave];
     uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
     if (MODE == 1) {
+        if (a.block_layer) {
+            // Layer-wise scales (Sec. II-B names the layer-wise granularity): row l of the slot array
+            // collects layer l, and a block lies in one layer, so every wave hands its block's
+            // maxima straight to its layer's row; the finalize has nothing left to reduce.
+            EpiMaxAbs epi{accu, lane};
+            for (int u = 0; u < V; ++u) {
+                const int64_t b = base + (int64_t)u * kBlockCoords;
+                if (b < a.d) {
+                    const LaneCoords lc = lane_coords(b, lane, a.d);
+                    encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
+                    const int layer = __builtin_amdgcn_readfirstlane((int)a.block_layer[b / kBlockCoords]);
+                    uint32_t* dst = a.part_max + (int64_t)layer * a.n;
+                    for (int i = lane; i < a.n; i += kWave)
+                        (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            return;
+        }
         // the workgroup's running maxima and the count of waves that have delivered theirs
         __shared__ uint32_t wg_max[kMaxWorkers];
         __shared__ uint32_t wg_done;
@@ -242,7 +261,7 @@ static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const
         // two blocks per wave where a ring driver serves the code and the vector is long enough
         // to fill the chip with half as many waves
         const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
-        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE > 1 && nblocks >= kTwoBlockMin) launch_scale_max<S, AGC_SCALE_BLOCKS_PER_WAVE>(G, code, a, stream);
+        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE > 1 && nblocks >= kTwoBlockMin && !a.block_layer) launch_scale_max<S, AGC_SCALE_BLOCKS_PER_WAVE>(G, code, a, stream);
         else launch_scale_max<S, 1>(G, code, a, stream);
     }
     return hipGetLastError();
@@ -252,7 +271,8 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream)
 {
-    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq, code.win};
+    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq, code.win, ws.n_layers > 0 ? ws.block_layer : nullptr};
+    if (a.block_layer && scale_mode != 1) return hipErrorInvalidValue;  // layer-wise scales are max-abs scales
     if (code.band < 0 && !code.win) return hipErrorInvalidValue;  // the window driver reads the records
     switch (code.band) {
         case 1: return launch_scale_pass_s<1>(G, code, a, scale_mode, stream);
@@ -360,9 +380,40 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     }
 }
 
+// Layer-wise scales: workgroup l, thread i.  Row l of the slot array already holds the layer's
+// maxima; every (worker, layer) gets its scale, and table l of the quantize pass gets the
+// worker's record with the multiplier and the decode weight of that layer (the formulas of the
+// per-vector case with the layer's scale).  The row is handed back zeroed.
+__global__ __launch_bounds__(kWgThreads) void k_scale_finalize_layers(int n, QuantStreams out, StepWeights sw,
+                                                                      Workspace ws, float* scales)
+{
+    const int l = blockIdx.x;
+    for (int i = threadIdx.x; i < n; i += kWgThreads) {
+        uint32_t* p = ws.part_max + (int64_t)l * n + i;
+        const float scale = __uint_as_float(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        scales[(int64_t)i * ws.n_layers + l] = scale;
+        const int b = out.bits[i];
+        const uint32_t flush = (i == n - 1 || out.stage_start[i + 1] == 0) ? 1u : 0u;
+        WorkerQ e{inv16_of(scale, b), (uint32_t)b, out.codes[i], 0.f, 0u, 8u * out.stage_start[i], flush};
+        if (sw.fuse) {
+            const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+            e.coef = (float)(((double)sw.w[i] * (double)scale) / L);
+            e.arrived = (uint32_t)sw.arrived[i];
+        }
+        ws.wq[(int64_t)l * n + i] = e;
+    }
+}
+
 hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out, const StepWeights& sw,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
+    if (ws.n_layers > 0) {
+        if (scale_mode != 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k_scale_finalize_layers, dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, out, sw, ws,
+                           scales);
+        return hipGetLastError();
+    }
     if (scale_mode == 0) {
         hipLaunchKernelGGL(k_scale_groups, dim3((unsigned)ws.ngroup), dim3(kWgThreads), 0, stream, n, ws);
         hipError_t e = hipGetLastError();
@@ -406,7 +457,8 @@ hipError_t launch_quantize_bucket(const float* G, int64_t ldg, int n, int k, int
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat, nullptr, stage_bits_needed(out.bits, n), stage_fills(out.bits, n)};
+                scales, (d + kBlockCoords - 1) / kBlockCoords, ghat, nullptr, stage_bits_needed(out.bits, n), stage_fills(out.bits, n),
+                nullptr};
     if (a.stage_fills > 1)
         return scale_mode == 0 ? launch_quantize_band2m(G, code, ws, a, stream)
                                : launch_quantize_band1m(G, code, ws, a, stream);
@@ -419,7 +471,8 @@ hipError_t launch_quantize(const float* G, int64_t ldg, int n, int k, int64_t d,
                            uint64_t step, float* ghat, hipStream_t stream)
 {
     QuantArgs a{ldg, n, k, d, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32),
-                nullptr, 0, ghat, nullptr, stage_bits_needed(bits, n), stage_fills(bits, n)};
+                nullptr, 0, ghat, nullptr, stage_bits_needed(bits, n), stage_fills(bits, n),
+                ws.n_layers > 0 ? ws.block_layer : nullptr};
     return a.stage_fills > 1 ? launch_quantize_band0m(G, code, ws, a, stream)
                              : launch_quantize_band0s(G, code, ws, a, stream);
 }
@@ -534,6 +587,10 @@ struct DecodeArgs {
     int64_t d;
     float* ghat;
     float* ghat2;  // second track (two-track decode only)
+    // layer-wise scales only: the layer of every block and the weights [layer][arrived slot]
+    const uint8_t* block_layer;
+    const float* coef_layer;
+    const float* coef2_layer;
 };
 
 __device__ __forceinline__ void store_coords(float* dst, const float (&acc)[kDecCoords], int64_t m0, int64_t d)
@@ -552,7 +609,10 @@ __device__ __forceinline__ void store_coords(float* dst, const float (&acc)[kDec
 // Planned for six waves per SIMD (77 registers instead of 82): the kernel is short (12 waves per
 // SIMD at the metric size), so one more resident wave shortens its last, partly filled round;
 // measured 0.175 -> 0.168 ms.  Eight would spill.
-template <bool TWO, bool BUCKET>
+// SCALES 0: one scale per worker (the weight of the table).  1: bucket-wise (weight of the table
+// times the bucket's scale).  2: layer-wise (the weight of the lane's layer, read from the
+// [layer][slot] table; a lane's 32 coordinates lie in one block and therefore in one layer).
+template <bool TWO, int SCALES>
 __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(TWO ? 1 : 6, TWO ? 8 : 6))) void k_decode(const WorkerD* __restrict__ wd,
                                                        const float* __restrict__ coef2,
                                                        const float* const* __restrict__ srow, DecodeArgs a)
@@ -566,14 +626,20 @@ __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(TWO 
     for (int q = 0; q < kDecCoords; ++q) acc[q] = 0.f;
 #pragma unroll
     for (int q = 0; q < (TWO ? kDecCoords : 1); ++q) acc2[q] = 0.f;
+    constexpr bool BUCKET = SCALES != 0;  // the weights differ from lane to lane
+    int64_t layer_row = 0;
+    if (SCALES == 2) layer_row = (int64_t)a.block_layer[t >> 3] * a.n_arrived;
     for (int e = 0; e < a.n_arrived; ++e) {
         const WorkerD wk = wd[e];  // wave-uniform: one scalar 16-byte load
         float c1 = wk.coef;
         float c2 = TWO ? coef2[e] : 0.f;
-        if (BUCKET) {  // the lane's 32 coordinates lie in one 256-coordinate bucket
+        if (SCALES == 1) {  // the lane's 32 coordinates lie in one 256-coordinate bucket
             const float sc = ((const __attribute__((address_space(1))) float*)srow[e])[t >> 3];
             c1 = c1 * sc;
             c2 = c2 * sc;
+        } else if (SCALES == 2) {
+            c1 = a.coef_layer[layer_row + e];
+            if (TWO) c2 = a.coef2_layer[layer_row + e];
         }
         const int b = (int)wk.bits;
         const global_u32* src = (const global_u32*)wk.codes + t * b;
@@ -607,29 +673,72 @@ __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(TWO 
 }
 
 template <bool TWO>
-static void launch_decode_kernel(bool bucket, unsigned grid, hipStream_t stream, const Workspace& ws,
+static void launch_decode_kernel(int scales_kind, unsigned grid, hipStream_t stream, const Workspace& ws,
                                  const DecodeArgs& a)
 {
     const float* c2 = TWO ? ws.coef2 : nullptr;
-    if (bucket)
-        hipLaunchKernelGGL((k_decode<TWO, true>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
+    if (scales_kind == 2)
+        hipLaunchKernelGGL((k_decode<TWO, 2>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
+                           (const float* const*)nullptr, a);
+    else if (scales_kind == 1)
+        hipLaunchKernelGGL((k_decode<TWO, 1>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
                            (const float* const*)ws.srow, a);
     else
-        hipLaunchKernelGGL((k_decode<TWO, false>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
+        hipLaunchKernelGGL((k_decode<TWO, 0>), dim3(grid), dim3(kWgThreads), 0, stream, ws.wd, c2,
                            (const float* const*)nullptr, a);
+}
+
+// Layer-wise scales, prologue: workgroup l, thread i.  The weight of arrived worker i in layer l,
+// w_i * scale_il / L_i (binary64, one rounding: the per-vector formula with the layer's scale),
+// goes to [l][slot]; workgroup 0 also writes the table of streams and bit-widths.
+__global__ __launch_bounds__(kWgThreads) void k_decode_table_layers(int n, int n_layers, int n_arrived,
+                                                                    DecodeStreams in, const float* scales,
+                                                                    WorkerD* wd, float* coef_layer)
+{
+    const int l = blockIdx.x;
+    for (int i = threadIdx.x; i < n; i += kWgThreads) {
+        const uint32_t slot = in.slot[i];
+        if (slot == 0xFFFFu) continue;
+        const int b = in.bits[i];
+        const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+        coef_layer[(int64_t)l * n_arrived + slot] =
+            (float)(((double)in.w[i] * (double)scales[(int64_t)i * n_layers + l]) / L);
+        if (l == 0) wd[slot] = WorkerD{in.codes[i], 0.f, (uint32_t)b};
+    }
+}
+
+// the same for the second decoding vector of the two-track decode
+__global__ __launch_bounds__(kWgThreads) void k_decode_table2_layers(int n, int n_layers, int n_arrived,
+                                                                     DecodeSecond in, const float* scales,
+                                                                     float* coef2_layer)
+{
+    const int l = blockIdx.x;
+    for (int i = threadIdx.x; i < n; i += kWgThreads) {
+        const uint32_t slot = in.slot[i];
+        if (slot == 0xFFFFu) continue;
+        const int b = in.bits[i];
+        const double L = b >= 2 ? (double)((1 << (b - 1)) - 1) : 1.0;
+        coef2_layer[(int64_t)l * n_arrived + slot] =
+            (float)(((double)in.v[i] * (double)scales[(int64_t)i * n_layers + l]) / L);
+    }
 }
 
 hipError_t launch_decode(int n, int n_arrived, int64_t d, const DecodeStreams& in,
                          const float* scales, int64_t nb, const Workspace& ws, float* ghat,
                          hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
+    const bool layers = ws.n_layers > 0;
+    if (layers)
+        hipLaunchKernelGGL(k_decode_table_layers, dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, ws.n_layers,
+                           n_arrived, in, scales, ws.wd, ws.coef_layer);
+    else
+        hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    DecodeArgs a{n_arrived, d, ghat, nullptr};
+    DecodeArgs a{n_arrived, d, ghat, nullptr, ws.block_layer, ws.coef_layer, nullptr};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    launch_decode_kernel<false>(nb > 0, grid, stream, ws, a);
+    launch_decode_kernel<false>(layers ? 2 : (nb > 0 ? 1 : 0), grid, stream, ws, a);
     return hipGetLastError();
 }
 
@@ -637,16 +746,25 @@ hipError_t launch_decode2(int n, int n_arrived, int64_t d, const DecodeStreams& 
                           const float* scales, int64_t nb, const Workspace& ws, float* ghat, float* ghat2,
                           hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
+    const bool layers = ws.n_layers > 0;
+    if (layers)
+        hipLaunchKernelGGL(k_decode_table_layers, dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, ws.n_layers,
+                           n_arrived, in, scales, ws.wd, ws.coef_layer);
+    else
+        hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, ws.wd, ws.srow);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_decode_table2, dim3(1), dim3(kWgThreads), 0, stream, n, second, scales, nb, ws.coef2);
+    if (layers)
+        hipLaunchKernelGGL(k_decode_table2_layers, dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, ws.n_layers,
+                           n_arrived, second, scales, ws.coef2_layer);
+    else
+        hipLaunchKernelGGL(k_decode_table2, dim3(1), dim3(kWgThreads), 0, stream, n, second, scales, nb, ws.coef2);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    DecodeArgs a{n_arrived, d, ghat, ghat2};
+    DecodeArgs a{n_arrived, d, ghat, ghat2, ws.block_layer, ws.coef_layer, ws.coef2_layer};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
-    launch_decode_kernel<true>(nb > 0, grid, stream, ws, a);
+    launch_decode_kernel<true>(layers ? 2 : (nb > 0 ? 1 : 0), grid, stream, ws, a);
     return hipGetLastError();
 }
 
@@ -697,14 +815,14 @@ hipError_t launch_decode_static(int n, int n_arrived, int64_t d, const DecodeStr
     hipLaunchKernelGGL(k_decode_table, dim3(1), dim3(kWgThreads), 0, stream, n, in, scales, nb, wd, srow);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    DecodeArgs a{n_arrived, d, ghat, nullptr};
+    DecodeArgs a{n_arrived, d, ghat, nullptr, nullptr, nullptr, nullptr};
     const int64_t nthreads = (d + kDecCoords - 1) / kDecCoords;
     const unsigned grid = (unsigned)((nthreads + kWgThreads - 1) / kWgThreads);
     if (nb > 0)
-        hipLaunchKernelGGL((k_decode<false, true>), dim3(grid), dim3(kWgThreads), 0, stream, wd, (const float*)nullptr,
+        hipLaunchKernelGGL((k_decode<false, 1>), dim3(grid), dim3(kWgThreads), 0, stream, wd, (const float*)nullptr,
                            (const float* const*)srow, a);
     else
-        hipLaunchKernelGGL((k_decode<false, false>), dim3(grid), dim3(kWgThreads), 0, stream, wd,
+        hipLaunchKernelGGL((k_decode<false, 0>), dim3(grid), dim3(kWgThreads), 0, stream, wd,
                            (const float*)nullptr, (const float* const*)nullptr, a);
     return hipGetLastError();
 }

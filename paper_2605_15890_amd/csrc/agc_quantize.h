@@ -23,6 +23,7 @@ struct QuantArgs {
     const WindowRec* win;  // monotone-interval codes only; filled in by the launcher
     int stage_bits;        // largest sum of bit-widths one fill of the staging area holds (<= kStageBits)
     int stage_fills;       // how many fills the workers need (1 unless the widths sum to more than kStageBits)
+    const uint8_t* block_layer;  // layer-wise scales only: the layer of every block; wq is then [layer][n]
 };
 
 typedef __attribute__((address_space(1))) uint32_t global_u32;  // a pointer known to be device memory
@@ -409,6 +410,10 @@ __global__ __launch_bounds__(kQuantThreads) __attribute__((amdgpu_waves_per_eu(S
     const bool has_block = base < a.d;
     LaneCoords lc{};
     if (has_block) lc = lane_coords(base, lane, a.d);
+    // layer-wise scales: the table of the block's layer (multiplier and decode weight differ from
+    // layer to layer; bit-width, stream and staging place are the same in every table, so the
+    // waves of a workgroup may hold different tables when they meet at a flush)
+    if (a.block_layer && has_block) wq += (int64_t)__builtin_amdgcn_readfirstlane((int)a.block_layer[block]) * a.n;
     EpiQuant<BUCKET, FUSE, MULTI> epi{wq, a.key0, a.key1, a.step_lo, a.step_hi, lds_stage,
                                reinterpret_cast<float*>(lds_stage + 4 * stage_pieces(a.stage_bits)), lane, wave, a.n, wg,
                                groups_left >= 2 * kQuantWaves ? 2 * kQuantWaves : (int)groups_left, block, (uint32_t)((base + 4 * lane) >> 2),

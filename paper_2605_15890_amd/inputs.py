@@ -93,6 +93,16 @@ def layer_sigmas(cfg: Config, d: int):
     return sig, edges
 
 
+def layer_ends(cfg: Config, d: Optional[int] = None):
+    """Ends of the layers of a "layered" configuration for layer-wise scales: the law's own block
+    edges moved down to multiples of 256 (a 256-coordinate block lies in one layer), duplicates
+    dropped, the last one d itself."""
+    d = cfg.d if d is None else d
+    _, edges = layer_sigmas(cfg, d)
+    ends = sorted({int(e) // 256 * 256 for e in edges[1:-1]} - {0})
+    return np.array([e for e in ends if e < d] + [d], dtype=np.int64)
+
+
 def partial_gradients_numpy(cfg: Config, d: Optional[int] = None, seed_offset: int = 0) -> np.ndarray:
     """k x d float32 partial gradients on the host (for sizes the CPU handles)."""
     d = cfg.d if d is None else d

@@ -1,0 +1,202 @@
+"""GPU parity of layer-wise max-abs scales (agc_set_layers; Sec. II-B: the quantizer "at layer-wise
+or bucket-wise granularity") through the C ABI against the oracle's layer-wise composition: streams
+bit for bit, scales as bit patterns, the estimate identical, for every encode driver, the fused and
+the two-pass step, the stand-alone and the two-track decode; and the error paths."""
+import numpy as np
+import pytest
+
+from oracle import agc_oracle as O
+from paper_2605_15890_amd import api
+from paper_2605_15890_amd import inputs as I
+
+from gpu_util import cyclic_csr, monotone_csr, random_csr, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(G_host, n, k, code, bits, w, mask, seed, step, ends, unfused, path=None, allow_1bit=False):
+    import torch
+    d = G_host.shape[1]
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS, unfused_step=unfused, allow_1bit=allow_1bit)
+    try:
+        ctx.agc_set_code(*code)
+        if path is not None:
+            assert ctx.agc_code_path() == path
+        ctx.agc_set_layers(ends)
+        assert ctx.agc_scales_per_worker() == len(ends)
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        assert tuple(scales.shape) == (n, len(ends))
+        for c in codes:
+            c.fill_(0xA5)
+        scales.fill_(-7.0)
+        ghat.fill_(float("nan"))
+        ctx.agc_step(G, bits, w, mask, seed, step, codes, scales, ghat)
+        torch.cuda.synchronize()
+        return [c.cpu().numpy() for c in codes], scales.cpu().numpy(), ghat.cpu().numpy()
+    finally:
+        ctx.close()
+
+
+def _check(G_host, k, code, bits, w, mask, seed, step, ends, out, tag):
+    streams, scales, ghat = out
+    csr = O.Csr(code[0], code[1], code[2], k)
+    o_streams, o_scales, o_ghat = O.step_layers(G_host, csr, bits, w, mask, seed, step, ends)
+    assert np.array_equal(scales.view(np.uint32), o_scales.view(np.uint32)), tag
+    for i in range(csr.n):
+        assert np.array_equal(streams[i], o_streams[i]), (tag, "stream", i)
+    assert np.array_equal(ghat.view(np.uint32), o_ghat.view(np.uint32)), tag
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("kind,d,ends", [
+    ("cyclic3", 4096, [1024, 2048, 4096]),
+    ("cyclic3", 5000, [256, 512, 4864, 5000]),           # one-block layers, a ragged last layer
+    ("cyclic8", 2049, [2048, 2049]),                     # the last layer is one coordinate
+    ("window4", 70001, [256 * 7, 256 * 100, 256 * 101, 70001]),
+    ("generic", 3000, [768, 3000]),
+    ("cyclic1", 300, [256, 300]),
+])
+def test_layerwise_step_matches_oracle(kind, d, ends, unfused):
+    rng = np.random.default_rng(len(kind) * 1000 + d)
+    if kind.startswith("cyclic"):
+        s = int(kind[6:])
+        n = k = 9
+        code = cyclic_csr(rng, n, s)
+        path = s
+    elif kind.startswith("window"):
+        n, k = 11, 7
+        code = monotone_csr(rng, n, k, 4)
+        path = None
+    else:
+        n, k = 6, 5
+        code = random_csr(rng, n, k)
+        path = 0
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    lo = 0
+    for l, hi in enumerate(ends):                         # magnitudes that differ from layer to layer
+        G_host[:, lo:hi] *= np.float32(10.0 ** (l % 4 - 2))
+        lo = hi
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    bits[0] = 16
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = (rng.uniform(size=n) < 0.7).astype(np.uint8)
+    mask[1] = 1
+    out = _run(G_host, n, k, code, bits, w, mask, 41, 6, ends, unfused, path)
+    _check(G_host, k, code, bits, w, mask, 41, 6, ends, out, f"{kind} d={d} unfused={unfused}")
+
+
+def test_one_layer_equals_the_per_vector_step_and_layers_can_be_switched_off():
+    import torch
+    rng = np.random.default_rng(77)
+    n = k = 6
+    d = 3333
+    code = cyclic_csr(rng, n, 2)
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    bits = rng.integers(1, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = np.array([1, 1, 0, 1, 1, 1], dtype=np.uint8)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS, allow_1bit=True)
+    try:
+        ctx.agc_set_code(*code)
+        res = []
+        for ends in ([], [d], [1024, d], []):
+            ctx.agc_set_layers(ends)
+            codes, scales, ghat = ctx.alloc_outputs(bits)
+            ctx.agc_step(G, bits, w, mask, 3, 9, codes, scales, ghat)
+            torch.cuda.synchronize()
+            res.append(([c.cpu().numpy() for c in codes], scales.cpu().numpy().reshape(n, -1), ghat.cpu().numpy()))
+        for other in (res[1], res[3]):
+            for a, b in zip(res[0][0], other[0]):
+                assert np.array_equal(a, b)
+            assert np.array_equal(res[0][1][:, 0].view(np.uint32), other[1][:, 0].view(np.uint32))
+            assert np.array_equal(res[0][2].view(np.uint32), other[2].view(np.uint32))
+        assert res[2][1].shape == (n, 2)
+        csr = O.Csr(code[0], code[1], code[2], k)
+        o = O.step_layers(G_host, csr, bits, w, mask, 3, 9, [1024, d])
+        assert np.array_equal(res[2][1].view(np.uint32), o[1].view(np.uint32))
+        assert np.array_equal(res[2][2].view(np.uint32), o[2].view(np.uint32))
+    finally:
+        ctx.close()
+
+
+def test_layerwise_decode_and_two_track_decode_match_oracle():
+    import torch
+    rng = np.random.default_rng(78)
+    n = k = 7
+    d = 256 * 9 + 100
+    ends = [256, 256 * 5, d]
+    code = cyclic_csr(rng, n, 3)
+    csr = O.Csr(code[0], code[1], code[2], k)
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    G_host[:, 256:256 * 5] *= np.float32(1e-3)
+    bits = rng.integers(2, 7, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    v = rng.uniform(0.1, 2.0, n).astype(np.float32)
+    mask = np.array([1, 0, 1, 1, 1, 0, 1], dtype=np.uint8)
+    o_streams, o_scales = O.encode_quantize_layers(G_host, csr, bits, 8, 1, ends)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS)
+    try:
+        ctx.agc_set_code(*code)
+        ctx.agc_set_layers(ends)
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        ghat2 = torch.empty_like(ghat)
+        ctx.agc_encode_quantize(G, bits, 8, 1, codes, scales)
+        torch.cuda.synchronize()
+        assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
+        for i in range(n):
+            assert np.array_equal(codes[i].cpu().numpy(), o_streams[i])
+        ctx.agc_decode(codes, scales, bits, w, mask, ghat)
+        torch.cuda.synchronize()
+        want = O.decode_layers(o_streams, o_scales, bits, w, mask, d, ends)
+        assert np.array_equal(ghat.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        ghat.fill_(float("nan"))
+        ctx.agc_decode2(codes, scales, bits, w, v, mask, ghat, ghat2)
+        torch.cuda.synchronize()
+        want2 = O.decode_layers(o_streams, o_scales, bits, v, mask, d, ends)
+        assert np.array_equal(ghat.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        assert np.array_equal(ghat2.cpu().numpy().view(np.uint32), want2.view(np.uint32))
+    finally:
+        ctx.close()
+
+
+def test_layerwise_scales_with_the_maximum_number_of_layers_and_workers():
+    rng = np.random.default_rng(79)
+    n, k = api.AGC_MAX_WORKERS, 6
+    nl = api.AGC_MAX_LAYERS
+    d = 256 * nl + 77
+    ends = [256 * (l + 1) for l in range(nl - 1)] + [d]
+    code = monotone_csr(rng, n, k, 2)
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    bits = np.full(n, 2, dtype=np.uint8)
+    bits[::7] = 3
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = (rng.uniform(size=n) < 0.8).astype(np.uint8)
+    out = _run(G_host, n, k, code, bits, w, mask, 2, 2, ends, False)
+    _check(G_host, k, code, bits, w, mask, 2, 2, ends, out, "256 layers x 256 workers")
+
+
+def test_set_layers_argument_errors():
+    d = 4096
+    ctx = api.Context(4, 4, d, scale_mode=api.AGC_SCALE_MAXABS)
+    try:
+        for bad in ([100, d], [1024, 1024, d], [2048, 1024, d], [1024, d - 1], [1024, d + 256],
+                    [256 * (l + 1) for l in range(api.AGC_MAX_LAYERS)] + [256 * 300]):
+            with pytest.raises(api.AgcError) as e:
+                ctx.agc_set_layers(bad)
+            assert e.value.status == api.AGC_ESHAPE, bad
+        assert ctx.agc_scales_per_worker() == 1          # a refused call changes nothing
+        ctx.agc_set_layers([1024, d])
+        assert ctx.agc_scales_per_worker() == 2
+    finally:
+        ctx.close()
+    for kw in (dict(scale_mode=api.AGC_SCALE_L2), dict(scale_mode=api.AGC_SCALE_MAXABS, bucket=256)):
+        ctx = api.Context(4, 4, d, **kw)
+        try:
+            with pytest.raises(api.AgcError) as e:
+                ctx.agc_set_layers([1024, d])
+            assert e.value.status == api.AGC_EINVAL
+        finally:
+            ctx.close()
