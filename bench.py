@@ -8,13 +8,13 @@ dominant kernel (HIP-event durations measured in the timed region) and the CPU o
 on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--scale maxabs|l2]
-                    [--code cyclic|interval] [--bucket 0|256] [--two-pass] [--no-variants]
+                    [--code cyclic|interval] [--bucket 0|256] [--layers N] [--two-pass] [--no-variants]
                     [--no-cpu-baseline]
 
 The default run (no flags) times the metric configuration (resnet50-sized: n = k = 64, s = 4,
 d = 25.6 M, cyclic code, max-abs scale per vector, fused step) and then, in the same process and
 on the same inputs, the other forms the library offers at that size (two-pass step, Euclidean
-scale, the paper's interval code, bucket-wise scales), a plain copy and the bare access pattern of
+scale, the paper's interval code, layer-wise and bucket-wise scales), a plain copy and the bare access pattern of
 the two streaming passes, so that every number quoted anywhere comes from one timed line.
 """
 import argparse
@@ -174,7 +174,13 @@ def alg_bytes_of(n, k, d, bits, masks, bucket, two_pass):
     }
 
 
-def time_variant(api, I, cfg, G, bufs, p, bits, code, w, scale, bucket, two_pass, K, W, seed):
+def equal_layers(d, count):
+    """Ends of `count` layers of near-equal size, all but the last multiples of 256."""
+    ends = sorted({int(round(d * (l + 1) / count)) // 256 * 256 for l in range(count - 1)} - {0})
+    return np.array([e for e in ends if e < d] + [d], dtype=np.int64)
+
+
+def time_variant(api, I, cfg, G, bufs, p, bits, code, w, scale, bucket, two_pass, K, W, seed, layers=0):
     """W warm-up steps, K timed steps without any event between the kernels (wall clock bracketed by
     device synchronisation: this is the step time), then K more steps with a HIP-event pair around
     every kernel on the stream the kernels run on (their average durations; the event records
@@ -184,9 +190,11 @@ def time_variant(api, I, cfg, G, bufs, p, bits, code, w, scale, bucket, two_pass
     scale_mode = api.AGC_SCALE_MAXABS if scale == "maxabs" else api.AGC_SCALE_L2
     ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, bucket=bucket, unfused_step=two_pass)
     ctx.agc_set_code(*code)
+    if layers:
+        ctx.agc_set_layers(equal_layers(d, layers))
     codes, ghat = bufs
     per = ctx.agc_scales_per_worker()
-    scales = torch.empty((n, per) if bucket else n, dtype=torch.float32, device=G.device)
+    scales = torch.empty((n, per) if per > 1 else n, dtype=torch.float32, device=G.device)
     masks = [I.arrival_mask(cfg, p, t) for t in range(W + 2 * K)]     # sampled outside the timed regions
     for t in range(W):
         ctx.agc_step(G, bits, w, masks[t], seed, t, codes, scales, ghat)
@@ -299,6 +307,8 @@ def main():
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
     ap.add_argument("--bucket", type=int, default=0, choices=[0, 256],
                     help="256: one scale per 256-coordinate bucket (single pass over G); 0: one per vector")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="N > 0: layer-wise max-abs scales over N layers of equal size (agc_set_layers)")
     ap.add_argument("--two-pass", "--unfused", dest="two_pass", action="store_true",
                     help="run the step as two passes (stand-alone decode kernel) instead of the fused pass")
     ap.add_argument("--no-variants", action="store_true",
@@ -342,30 +352,33 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    main_r = time_variant(api, I, cfg, G, bufs, p, bits, code, w, args.scale, args.bucket, args.two_pass, K, W, seed)
+    main_r = time_variant(api, I, cfg, G, bufs, p, bits, code, w, args.scale, args.bucket, args.two_pass, K, W, seed,
+                          layers=args.layers)
     ms_per_step = main_r["ms_per_step"]
     grad_bytes = 4.0 * k * d
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
     roofline = roofline_of(main_r, tag_of(cfg, args.code, args.scale, args.bucket, args.two_pass))
 
     default_run = (args.workload == "resnet50" and args.scale == "maxabs" and args.code == "cyclic"
-                   and not args.bucket and not args.two_pass)
+                   and not args.bucket and not args.two_pass and not args.layers)
     variants = None
     if default_run and not args.no_variants:
         # the other forms of the step at the same size, same process, same inputs
         Kv = min(K, 20)
         variants = {}
         interval = build_problem(cfg, api, "interval")
-        for name, (vcode, vscale, vbucket, vtwo, ckind) in {
-            "two_pass": (code, "maxabs", 0, True, "cyclic"),
-            "l2": (code, "l2", 0, False, "cyclic"),
-            "interval": (interval[2], "maxabs", 0, False, "interval"),
-            "bucket256": (code, "maxabs", 256, False, "cyclic"),
-            "bucket256_l2": (code, "l2", 256, False, "cyclic"),
-            "interval_bucket256": (interval[2], "maxabs", 256, False, "interval"),
+        for name, (vcode, vscale, vbucket, vtwo, ckind, vlayers) in {
+            "two_pass": (code, "maxabs", 0, True, "cyclic", 0),
+            "l2": (code, "l2", 0, False, "cyclic", 0),
+            "interval": (interval[2], "maxabs", 0, False, "interval", 0),
+            "layers128": (code, "maxabs", 0, False, "cyclic", 128),
+            "bucket256": (code, "maxabs", 256, False, "cyclic", 0),
+            "bucket256_l2": (code, "l2", 256, False, "cyclic", 0),
+            "interval_bucket256": (interval[2], "maxabs", 256, False, "interval", 0),
         }.items():
             vw = interval[3] if ckind == "interval" else w
-            r = time_variant(api, I, cfg, G, bufs, p, bits, vcode, vw, vscale, vbucket, vtwo, Kv, 3, seed)
+            r = time_variant(api, I, cfg, G, bufs, p, bits, vcode, vw, vscale, vbucket, vtwo, Kv, 3, seed,
+                             layers=vlayers)
             rf = roofline_of(r, tag_of(cfg, ckind, vscale, vbucket, vtwo))
             variants[name] = {
                 "ms_per_step": round(r["ms_per_step"], 4), "steps": Kv,
@@ -387,7 +400,7 @@ def main():
             roofline["dominant_vs_bare_pattern"] = round(ceil["pattern_read_write_ms"] / roofline["avg_launch_ms"], 4)
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.layers:   # the layer-wise oracle is a per-layer Python composition: not timed
         from oracle import agc_oracle as O
         csr = O.Csr(code[0], code[1], code[2], k)
         o_mode = O.SCALE_MAXABS if args.scale == "maxabs" else O.SCALE_L2
@@ -425,7 +438,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} workers, k={k} partitions, s={cfg.s}, d={d}, "
                                f"{cfg.law} gradients, bits sum {int(sum_b)} (mean {sum_b / n:.2f}), "
                                f"{args.code} code, {args.scale} scale"
-                               + (f" per {args.bucket}-coordinate bucket" if args.bucket else " per vector")
+                               + (f" per {args.bucket}-coordinate bucket" if args.bucket else
+                                  f" per layer ({args.layers} layers)" if args.layers else " per vector")
                                + (", two-pass step" if args.two_pass else ", fused step"),
                    "code_path": main_r["code_path"]},
         "coded_elements_per_s": round(n * d / (ms_per_step * 1e-3), 1),

@@ -219,6 +219,7 @@ agc_status agc_create(agc_ctx** out, int n, int k, int64_t d, const agc_opts* op
     if (o.bucket) {
         e = dev_alloc(&c->ws.srow, (size_t)n);  // the scales need no reduction workspace
     } else if (o.scale_mode == AGC_SCALE_MAXABS) {
+        c->ws.max_rows = agc::kMaxSlots;
         e = dev_alloc(&c->ws.part_max, (size_t)agc::kMaxSlots * n);
         if (e == hipSuccess) e = hipMemset(c->ws.part_max, 0, sizeof(uint32_t) * (size_t)agc::kMaxSlots * n);
         // the first scale pass may run on any stream of the caller, also one that does not order
@@ -374,14 +375,22 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
     uint8_t* d_layer = nullptr;
     agc::WorkerQ* d_wq = nullptr;
     float *d_c1 = nullptr, *d_c2 = nullptr;
+    uint32_t* d_max = nullptr;
     const size_t entries = (size_t)c->n * (size_t)n_layers;
+    const int rows = std::max(agc::kMaxSlots, n_layers * agc::kLayerSub);
     e = dev_alloc(&d_layer, (size_t)nblocks);
+    if (e == hipSuccess && rows > c->ws.max_rows) {  // several rows of running maxima per layer
+        e = dev_alloc(&d_max, (size_t)rows * c->n);
+        if (e == hipSuccess) e = hipMemset(d_max, 0, sizeof(uint32_t) * (size_t)rows * c->n);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
     if (e == hipSuccess) e = dev_alloc(&d_wq, entries);
     if (e == hipSuccess) e = dev_alloc(&d_c1, entries);
     if (e == hipSuccess) e = dev_alloc(&d_c2, entries);
     if (e == hipSuccess) e = hipMemcpy(d_layer, layer_of.data(), (size_t)nblocks, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         if (d_layer) (void)hipFree(d_layer);
+        if (d_max) (void)hipFree(d_max);
         if (d_wq) (void)hipFree(d_wq);
         if (d_c1) (void)hipFree(d_c1);
         if (d_c2) (void)hipFree(d_c2);
@@ -391,6 +400,11 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
     free_layers(c);
     if (c->ws.wq) (void)hipFree(c->ws.wq);
     c->ws.wq = d_wq;  // one table per layer; a later return to one scale per vector uses the first
+    if (d_max) {      // the larger array also serves the per-vector pass (its first kMaxSlots rows)
+        (void)hipFree(c->ws.part_max);
+        c->ws.part_max = d_max;
+        c->ws.max_rows = rows;
+    }
     c->ws.block_layer = d_layer;
     c->ws.coef_layer = d_c1;
     c->ws.coef2_layer = d_c2;

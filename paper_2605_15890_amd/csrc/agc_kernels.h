@@ -96,7 +96,8 @@ struct WorkerD {
 };
 
 struct Workspace {
-    uint32_t* part_max;   // [kMaxSlots][n] running max |f_i| as bit patterns, all zero between steps (max-abs scale)
+    uint32_t* part_max;   // [max_rows][n] running max |f_i| as bit patterns, all zero between steps (max-abs scale)
+    int max_rows;         // kMaxSlots, or n_layers * kLayerSub if that is more
     double* part_sq;      // [nseg][n]   per-segment sum of squares             (Euclidean scale)
     double* group_sq;     // [n][ngroup]
     double* super_sq;     // [n][nsuper]
@@ -115,7 +116,8 @@ struct Workspace {
 };
 
 constexpr int kMaxSlots = 256;  // rows of the max-abs array; a block folds into row (block mod kMaxSlots)
-constexpr int kMaxLayers = kMaxSlots;  // with layer-wise scales row l of the array belongs to layer l
+constexpr int kMaxLayers = 256;  // layer-wise scales: a block's layer fits a byte
+constexpr int kLayerSub = 16;    // with layer-wise scales layer l owns rows l*kLayerSub .. +kLayerSub-1 of the array
 
 struct QuantStreams {      // host arrays of the encode call, as kernel arguments of the finalize
     void* codes[kArgWorkers];

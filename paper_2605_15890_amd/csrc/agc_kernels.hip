@@ -137,24 +137,6 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
     double* accd = lds_acc[wave];
     uint32_t* accu = reinterpret_cast<uint32_t*>(lds_acc[wave]);
     if (MODE == 1) {
-        if (a.block_layer) {
-            // Layer-wise scales (Sec. II-B names the layer-wise granularity): row l of the slot array
-            // collects layer l, and a block lies in one layer, so every wave hands its block's
-            // maxima straight to its layer's row; the finalize has nothing left to reduce.
-            EpiMaxAbs epi{accu, lane};
-            for (int u = 0; u < V; ++u) {
-                const int64_t b = base + (int64_t)u * kBlockCoords;
-                if (b < a.d) {
-                    const LaneCoords lc = lane_coords(b, lane, a.d);
-                    encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
-                    const int layer = __builtin_amdgcn_readfirstlane((int)a.block_layer[b / kBlockCoords]);
-                    uint32_t* dst = a.part_max + (int64_t)layer * a.n;
-                    for (int i = lane; i < a.n; i += kWave)
-                        (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-            return;
-        }
         // the workgroup's running maxima and the count of waves that have delivered theirs
         __shared__ uint32_t wg_max[kMaxWorkers];
         __shared__ uint32_t wg_done;
@@ -162,23 +144,49 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
         if (threadIdx.x == 0) wg_done = 0u;
         __syncthreads();  // the only barrier: at the start, where no wave has anything to wait for
         EpiMaxAbs epi{accu, lane};
-        auto fold = [&]() {  // accu[i] was written by this wave's lane 0
-            for (int i = lane; i < a.n; i += kWave)
-                (void)__hip_atomic_fetch_max(wg_max + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // Layer-wise scales (Sec. II-B names the layer-wise granularity): layer l owns rows
+        // l*kLayerSub .. l*kLayerSub+kLayerSub-1 of the slot array (several rows, so that the
+        // workgroups that walk one layer at the same time do not all hit the same words).  The
+        // workgroup's LDS array collects the layer of the workgroup's first block; a wave whose
+        // blocks lie in another layer (a workgroup that straddles a boundary) hands its maxima to
+        // that layer's row itself.
+        const int64_t last_block = (a.d - 1) / kBlockCoords;
+        const int64_t wg_first = (int64_t)blockIdx.x * (WAVES * V);
+        const int layer0 = a.block_layer
+                               ? __builtin_amdgcn_readfirstlane((int)a.block_layer[wg_first < last_block ? wg_first : last_block])
+                               : 0;
+        const int sub = (int)(blockIdx.x % kLayerSub);
+        auto fold = [&](int layer) {  // accu[i] was written by this wave's lane 0
+            if (layer == layer0) {
+                for (int i = lane; i < a.n; i += kWave)
+                    (void)__hip_atomic_fetch_max(wg_max + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            } else {
+                uint32_t* dst = a.part_max + ((int64_t)layer * kLayerSub + sub) * a.n;
+                for (int i = lane; i < a.n; i += kWave)
+                    (void)__hip_atomic_fetch_max(dst + i, accu[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        };
+        auto layer_of = [&](int64_t first_coord) {
+            return a.block_layer ? __builtin_amdgcn_readfirstlane((int)a.block_layer[first_coord / kBlockCoords]) : 0;
         };
         if (base < a.d) {
-            if (V > 1 && S != 0 && base + V * kBlockCoords <= a.d) {
+            bool together = V > 1 && S != 0 && base + V * kBlockCoords <= a.d;
+            if (together && a.block_layer) {  // all V blocks in one layer
+                for (int u = 1; u < V; ++u)
+                    together = together && layer_of(base + (int64_t)u * kBlockCoords) == layer_of(base);
+            }
+            if (together) {
                 const LaneCoords lc = lane_coords(base, lane, a.d);  // every lane whole, in all V blocks
                 if constexpr (S > 0) encode_ring<S, AGC_SCALE_PREFETCH_ROWS2, RowN<V>>(G + base, a.ldg, a.k, val, lc, epi);
                 else if constexpr (S < 0) encode_window<-S, AGC_SCALE_PREFETCH_ROWS2, RowN<V>>(G + base, a.ldg, a.k, B, lc, epi);
-                fold();
+                fold(layer_of(base));
             } else {
                 for (int u = 0; u < V; ++u) {
                     const int64_t b = base + (int64_t)u * kBlockCoords;
                     if (b < a.d) {
                         const LaneCoords lc = lane_coords(b, lane, a.d);
                         encode_block<S>(G + b, a.ldg, a.n, a.k, B, lc, epi);
-                        fold();
+                        fold(layer_of(b));
                     }
                 }
             }
@@ -193,7 +201,8 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
         before = (uint32_t)__builtin_amdgcn_readfirstlane((int)before);
         if (before == (uint32_t)(WAVES - 1)) {
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            uint32_t* dst = a.part_max + ((int64_t)blockIdx.x & (kMaxSlots - 1)) * a.n;
+            uint32_t* dst = a.part_max + (a.block_layer ? (int64_t)layer0 * kLayerSub + sub
+                                                        : ((int64_t)blockIdx.x & (kMaxSlots - 1))) * a.n;
             for (int i = lane; i < a.n; i += kWave) {
                 const uint32_t m = __hip_atomic_load(wg_max + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 if (m != 0u) (void)__hip_atomic_fetch_max(dst + i, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -229,7 +238,7 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_clear_slots(uint32_t* slot
 
 hipError_t launch_scale_clear_slots(int n, const Workspace& ws, hipStream_t stream)
 {
-    const int count = n * kMaxSlots;
+    const int count = n * ws.max_rows;
     hipLaunchKernelGGL(k_scale_clear_slots, dim3((count + kWgThreads - 1) / kWgThreads), dim3(kWgThreads), 0, stream,
                        ws.part_max, count);
     return hipGetLastError();
@@ -261,7 +270,7 @@ static hipError_t launch_scale_pass_s(const float* G, const CodeDev& code, const
         // two blocks per wave where a ring driver serves the code and the vector is long enough
         // to fill the chip with half as many waves
         const int64_t nblocks = (a.d + kBlockCoords - 1) / kBlockCoords;
-        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE > 1 && nblocks >= kTwoBlockMin && !a.block_layer) launch_scale_max<S, AGC_SCALE_BLOCKS_PER_WAVE>(G, code, a, stream);
+        if (S != 0 && AGC_SCALE_BLOCKS_PER_WAVE > 1 && nblocks >= kTwoBlockMin) launch_scale_max<S, AGC_SCALE_BLOCKS_PER_WAVE>(G, code, a, stream);
         else launch_scale_max<S, 1>(G, code, a, stream);
     }
     return hipGetLastError();
@@ -380,18 +389,22 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
     }
 }
 
-// Layer-wise scales: workgroup l, thread i.  Row l of the slot array already holds the layer's
-// maxima; every (worker, layer) gets its scale, and table l of the quantize pass gets the
+// Layer-wise scales: workgroup l, thread i.  The kLayerSub rows of layer l in the slot array hold
+// the layer's maxima; every (worker, layer) gets its scale, and table l of the quantize pass gets the
 // worker's record with the multiplier and the decode weight of that layer (the formulas of the
-// per-vector case with the layer's scale).  The row is handed back zeroed.
+// per-vector case with the layer's scale).  The rows are handed back zeroed.
 __global__ __launch_bounds__(kWgThreads) void k_scale_finalize_layers(int n, QuantStreams out, StepWeights sw,
                                                                       Workspace ws, float* scales)
 {
     const int l = blockIdx.x;
     for (int i = threadIdx.x; i < n; i += kWgThreads) {
-        uint32_t* p = ws.part_max + (int64_t)l * n + i;
-        const float scale = __uint_as_float(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t m = 0u;
+        for (int r = 0; r < kLayerSub; ++r) {
+            uint32_t* p = ws.part_max + ((int64_t)l * kLayerSub + r) * n + i;
+            m = max(m, __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const float scale = __uint_as_float(m);
         scales[(int64_t)i * ws.n_layers + l] = scale;
         const int b = out.bits[i];
         const uint32_t flush = (i == n - 1 || out.stage_start[i + 1] == 0) ? 1u : 0u;

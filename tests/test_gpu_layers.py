@@ -200,3 +200,70 @@ def test_set_layers_argument_errors():
             assert e.value.status == api.AGC_EINVAL
         finally:
             ctx.close()
+
+
+def test_layerwise_scales_at_full_size_on_the_layered_workload():
+    """The resnet18-sized workload (d = 11.7 M, partial gradients whose magnitude changes by up to
+    10^3 from one of its 60 layers to the next) with one scale per layer and worker: every scale
+    against the oracle over the whole vector; codes and the estimate in windows placed around layer
+    boundaries, at both ends and at random; the two-pass step gives the same bytes."""
+    import torch
+    cfg = I.CONFIGS["resnet18"]
+    n, k, d = cfg.n, cfg.k, cfg.d
+    p = I.straggler_probs(cfg)
+    bits = I.random_bits(cfg)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    row_ptr, col, val, w = api.agc_build_cyclic_code(n, k, cfg.s, p, np.maximum(bits, 2), pc)
+    ends = I.layer_ends(cfg)
+    assert 50 <= len(ends) <= 60 and all(int(e) % 256 == 0 for e in ends[:-1]) and int(ends[-1]) == d
+    G = I.partial_gradients_torch(cfg, torch.device("cuda:0"))
+    step = 2
+    mask = I.arrival_mask(cfg, p, step)
+    outs = []
+    for unfused in (False, True):
+        ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS, allow_1bit=cfg.allow_1bit, unfused_step=unfused)
+        ctx.agc_set_code(row_ptr, col, val)
+        assert ctx.agc_code_path() == cfg.s
+        ctx.agc_set_layers(ends)
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        ctx.agc_step(G, bits, w, mask, cfg.philox_seed, step, codes, scales, ghat)
+        torch.cuda.synchronize()
+        outs.append((codes, scales, ghat))
+        ctx.close()
+    assert all(torch.equal(a, b) for a, b in zip(outs[0][0], outs[1][0]))
+    assert torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][2].view(torch.int32), outs[1][2].view(torch.int32))
+    print("[layers] steps done, copying to host", flush=True)
+    G_host = G.cpu().numpy()
+    streams = [c.cpu().numpy() for c in outs[0][0]]
+    scales_h = outs[0][1].cpu().numpy()
+    ghat_h = outs[0][2].cpu().numpy()
+    del G, outs
+    torch.cuda.empty_cache()
+    csr = O.Csr(row_ptr, col, val, k)
+    print("[layers] oracle scales", flush=True)
+    o_scales = O.scales_layers(G_host, csr, ends)
+    assert np.array_equal(scales_h.view(np.uint32), o_scales.view(np.uint32))
+    # the layers really differ: per worker the largest and the smallest layer scale are far apart
+    assert np.all(o_scales.max(axis=1) > 50 * o_scales.min(axis=1))
+    rng = np.random.default_rng(18)
+    ranges = O.layer_ranges(ends, d)
+    windows = [(0, 2048), (d - 2048, d)]
+    for l in (0, 1, 17, len(ends) - 2):                      # straddling a layer boundary
+        windows.append((int(ends[l]) - 1024, int(ends[l]) + 1024))
+    for _ in range(10):
+        m0 = int(rng.integers(0, d - 2048))
+        windows.append((m0, m0 + 2048))
+    flips = 0
+    for (m0, m1) in windows:
+        for (e0, e1), l in zip(ranges, range(len(ranges))):   # the part of the window inside layer l
+            a, b = max(m0, e0), min(m1, e1)
+            if a >= b:
+                continue
+            for i in range(n):
+                want = O.codes_range(G_host, csr, i, int(bits[i]), o_scales[i, l], cfg.philox_seed, step, a, b)
+                got = O.unpack_range(streams[i], int(bits[i]), a, b)
+                flips += int(np.count_nonzero(want != got))
+            o_gh = O.decode(streams, np.ascontiguousarray(o_scales[:, l]), bits, w, mask, d, a, b)
+            assert np.array_equal(o_gh.view(np.uint32), ghat_h[a:b].view(np.uint32)), (m0, l)
+    assert flips == 0, flips
