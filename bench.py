@@ -156,8 +156,9 @@ def bench_lsq(args):
     ctx.close()
 
 
-def tag_of(cfg, code, scale, bucket, two_pass):
-    return (f"{cfg.name}_{code}_{scale}" + (f"_bucket{bucket}" if bucket else "") + ("_two_pass" if two_pass else ""))
+def tag_of(cfg, code, scale, bucket, two_pass, layers=0):
+    return (f"{cfg.name}_{code}_{scale}" + (f"_bucket{bucket}" if bucket else "") + (f"_layers{layers}" if layers else "")
+            + ("_two_pass" if two_pass else ""))
 
 
 def alg_bytes_of(n, k, d, bits, masks, bucket, two_pass):
@@ -357,7 +358,7 @@ def main():
     ms_per_step = main_r["ms_per_step"]
     grad_bytes = 4.0 * k * d
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
-    roofline = roofline_of(main_r, tag_of(cfg, args.code, args.scale, args.bucket, args.two_pass))
+    roofline = roofline_of(main_r, tag_of(cfg, args.code, args.scale, args.bucket, args.two_pass, args.layers))
 
     default_run = (args.workload == "resnet50" and args.scale == "maxabs" and args.code == "cyclic"
                    and not args.bucket and not args.two_pass and not args.layers)
@@ -379,7 +380,7 @@ def main():
             vw = interval[3] if ckind == "interval" else w
             r = time_variant(api, I, cfg, G, bufs, p, bits, vcode, vw, vscale, vbucket, vtwo, Kv, 3, seed,
                              layers=vlayers)
-            rf = roofline_of(r, tag_of(cfg, ckind, vscale, vbucket, vtwo))
+            rf = roofline_of(r, tag_of(cfg, ckind, vscale, vbucket, vtwo, vlayers))
             variants[name] = {
                 "ms_per_step": round(r["ms_per_step"], 4), "steps": Kv,
                 "value_GBps": round(grad_bytes / (r["ms_per_step"] * 1e-3) / 1e9, 1),
