@@ -267,3 +267,41 @@ def test_layerwise_scales_at_full_size_on_the_layered_workload():
             o_gh = O.decode(streams, np.ascontiguousarray(o_scales[:, l]), bits, w, mask, d, a, b)
             assert np.array_equal(o_gh.view(np.uint32), ghat_h[a:b].view(np.uint32)), (m0, l)
     assert flips == 0, flips
+
+
+def test_layerwise_step_is_unbiased_on_gpu():
+    """E[g_hat] = sum_j g_j also with one scale per layer (constraint of problem P1): the tiny
+    configuration with three layers whose magnitudes are 10^2 apart, 1000 steps with fresh arrival
+    masks and draws; projections of the mean error on 8 fixed directions within 3 standard errors."""
+    import torch
+    cfg = I.CONFIGS["tiny"]
+    n, k, d, T = cfg.n, cfg.k, cfg.d, 1000
+    p = I.straggler_probs(cfg)
+    bits = I.random_bits(cfg)
+    pc = api.agc_phi_coef_balanced(p, int(bits.sum()))
+    row_ptr, col, val, w = api.agc_build_cyclic_code(n, k, cfg.s, p, bits, pc)
+    dev = torch.device("cuda:0")
+    G = I.partial_gradients_torch(cfg, dev)
+    G[:, :1024] *= 0.01
+    G[:, 2048:] *= 100.0
+    g = G.double().sum(dim=0)
+    gen = torch.Generator(device=dev).manual_seed(4711)
+    dirs = torch.randn((8, d), generator=gen, device=dev, dtype=torch.float64)
+    dirs[:4, 1024:] = 0.0                       # four directions see the small layer alone
+    dirs /= dirs.norm(dim=1, keepdim=True)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS)
+    try:
+        ctx.agc_set_code(row_ptr, col, val)
+        ctx.agc_set_layers([1024, 2048, d])
+        codes, scales, ghat = ctx.alloc_outputs(bits)
+        proj = torch.zeros((T, 8), dtype=torch.float64, device=dev)
+        for t in range(T):
+            ctx.agc_step(G, bits, w, I.arrival_mask(cfg, p, t), cfg.philox_seed, t, codes, scales, ghat)
+            proj[t] = dirs @ (ghat.double() - g)
+        torch.cuda.synchronize()
+    finally:
+        ctx.close()
+    ph = proj.cpu().numpy()
+    z = ph.mean(axis=0) / (ph.std(axis=0, ddof=1) / np.sqrt(T))
+    print("z(projections) =", np.round(z, 2), flush=True)
+    assert np.all(np.abs(z) < 3.0), z
