@@ -144,7 +144,8 @@ struct DecodeSecond {      // second decoding vector of the two-track decode (Se
     uint16_t slot[kArgWorkers];
 };
 
-// K1: per-segment partials of every worker's scale.  scale_mode: 0 Euclidean, 1 max-abs.
+// K1: partial results of every worker's scale (max-abs: running maxima in ws.part_max, per layer
+// with layer-wise scales; Euclidean: per-segment sums of squares).  scale_mode: 0 Euclidean, 1 max-abs.
 hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t d,
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream);

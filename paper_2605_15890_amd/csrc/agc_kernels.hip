@@ -1,9 +1,11 @@
 // gfx950 kernels of the approximate-gradient-coding hot path.
 //
 //   k_scale_pass      worker side, pass 1: stream G once, form f_i = sum_j a_ij g_j in registers
-//                     (Sec. II-A) and reduce each worker's scale per 1024-coordinate segment
-//   k_scale_finalize  fixed-order reduction of the segment partials -> scale_i and the
-//                     per-worker table (inv16_i, b_i, stream pointer) of the next pass
+//                     (Sec. II-A) and reduce each worker's scale: running maxima in a small
+//                     array (max-abs, also per layer), sums of squares per 1024-coordinate
+//                     segment (Euclidean)
+//   k_scale_finalize  the maxima, or a fixed-order reduction of the segment sums -> scale_i and
+//   (.._layers)       the per-worker table (inv16_i, b_i, stream pointer) of the next pass
 //   k_quantize        worker side, pass 2: stream G once more, re-form f_i, stochastic rounding
 //                     on the grid {0,1/L,..,1} (Sec. II-B) with Philox draws, variable-width
 //                     bit-packing, coalesced stores of the payload
