@@ -253,3 +253,27 @@ def test_optimal_cyclic_code_matches_the_oracle_optimum():
     assert saw_bound and saw_gap
     with pytest.raises(api.AgcError):
         api.agc_build_cyclic_code_opt(4, 5, 2, [0.1] * 4, [2] * 4, 0.2)
+
+
+def test_public_headers_compile_as_plain_c_and_as_cpp(tmp_path):
+    """The boundary is a C ABI: both headers must be valid C99 (no C++-isms outside the extern "C"
+    guards) and valid C++, on their own, with warnings as errors."""
+    import shutil
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    src_c = tmp_path / "use_headers.c"
+    src_c.write_text('#include "agc.h"\n#include "agc_debug.h"\n'
+                     'static agc_opts o;\nint use(void) { agc_ctx *c = 0; (void)c; return o.bucket + AGC_MAX_LAYERS + AGC_NUM_KERNELS; }\n')
+    src_cpp = tmp_path / "use_headers.cpp"
+    src_cpp.write_text(src_c.read_text())
+    gcc, gxx = shutil.which("gcc"), shutil.which("g++")
+    assert gcc and gxx
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src_c)],
+                   check=True)
+    subprocess.run([gxx, "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src_cpp)],
+                   check=True)
+    # each header also stands alone
+    for h in ("agc.h", "agc_debug.h"):
+        one = tmp_path / ("only_" + h.replace(".h", ".c"))
+        one.write_text(f'#include "{h}"\nint main(void) {{ return 0; }}\n')
+        subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(one)], check=True)
