@@ -292,9 +292,18 @@ def measured_ceilings(api, G, k, d, scratch):
     ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=True))
     out["pattern_read_write_ms"] = round(ms, 4)
     out["pattern_read_write_GBps"] = round((g_bytes + w_bytes) / (ms * 1e-3) / 1e9, 1)
+    # the same at the quantize pass's occupancy (four waves per SIMD), bare and with about its arithmetic per row
+    ms = timed(lambda: api.agc_debug_stream_rows(G, 0, scratch, waves_per_simd=4))
+    out["pattern_read_4waves_ms"] = round(ms, 4)
+    ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=True, waves_per_simd=4))
+    out["pattern_read_write_4waves_ms"] = round(ms, 4)
+    for fma in (40, 100):
+        ms = timed(lambda: api.agc_debug_stream_rows(G, piece, scratch, wg_flush=True, waves_per_simd=4, fma_per_row=fma))
+        out[f"pattern_read_write_4waves_fma{fma}_ms"] = round(ms, 4)
     out["pattern_note"] = (f"bare row walk over G ({g_bytes / 1e9:.2f} GB), one block per wave or two (the max-abs scale pass's form); with writes: plus {w_bytes / 1e9:.3f} GB "
                            f"in {piece}-byte pieces per block to {k} streams, stored per wave after every row "
-                           f"(per_wave) or per workgroup as {4 * piece}-byte lines after a barrier (the quantize pass's form)")
+                           f"(per_wave) or per workgroup as {4 * piece}-byte lines after a barrier (the quantize pass's form); "
+                           f"4waves: the kernel built for four waves per SIMD; fmaN: N dependent multiply-adds per row and lane")
     return out
 
 
@@ -399,6 +408,9 @@ def main():
         # the dominant kernel against the bare pattern with the same kind of traffic
         if "pattern_read_write_ms" in ceil and roofline["kernel"] == "quantize":
             roofline["dominant_vs_bare_pattern"] = round(ceil["pattern_read_write_ms"] / roofline["avg_launch_ms"], 4)
+            # ... and against the same pattern at the pass's occupancy carrying about the pass's arithmetic per row
+            roofline["dominant_vs_pattern_with_arithmetic"] = round(
+                ceil["pattern_read_write_4waves_fma100_ms"] / roofline["avg_launch_ms"], 4)
 
     cpu_baseline = None
     if not args.no_cpu_baseline and not args.layers:   # the layer-wise oracle is a per-layer Python composition: not timed

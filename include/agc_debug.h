@@ -54,13 +54,20 @@ agc_status agc_calibration_copy(void *dst_dev, const void *src_dev, int64_t byte
  *   blocks_per_wave: 1, or 2 with piece_bytes == 0: a wave walks two neighbouring blocks at once
  *                  (two loads per row, 1 KiB apart, two rows in flight), the form of the max-abs
  *                  scale pass on long vectors; only whole pairs of blocks are read then.
+ *   waves_per_simd: 0 = whatever fits (eight), 4 = the kernel is built for four waves per SIMD, the
+ *                  occupancy the quantize pass runs at (the memory system delivers most there);
+ *   fma_per_row:   0, 40 or 100: that many dependent multiply-adds per row and lane between the
+ *                  loads, standing in for the arithmetic of a pass (the quantize pass issues about
+ *                  ninety vector instructions per row and lane); only with waves_per_simd == 4,
+ *                  wg_flush != 0, piece_bytes > 0 and blocks_per_wave == 1.
  * Only whole blocks are touched (floor(d/256) of them).  What this kernel reaches is what the
  * memory system delivers for that traffic, whatever the arithmetic on top of it.
  *   G_dev    device, k x d binary32, row stride ldg (multiple of 4), 16-byte aligned; read-only
  *   out_dev  device, 16-byte aligned, at least max(16, k * floor(d/256) * piece_bytes) bytes
  */
 agc_status agc_debug_stream_rows(const float *G_dev, int64_t ldg, int k, int64_t d, int piece_bytes,
-                                 int wg_flush, int blocks_per_wave, void *out_dev, void *hip_stream);
+                                 int wg_flush, int blocks_per_wave, int waves_per_simd, int fma_per_row,
+                                 void *out_dev, void *hip_stream);
 
 #ifdef __cplusplus
 }

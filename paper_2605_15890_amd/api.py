@@ -104,7 +104,7 @@ def load():
     L.agc_gd_update.restype = C.c_int
     L.agc_calibration_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
     L.agc_calibration_copy.restype = C.c_int
-    L.agc_debug_stream_rows.argtypes = [_vp, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp]
+    L.agc_debug_stream_rows.argtypes = [_vp, C.c_int64, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp]
     L.agc_debug_stream_rows.restype = C.c_int
     L.agc_profile_enable.argtypes = [_vp, C.c_int]
     L.agc_profile_enable.restype = C.c_int
@@ -467,17 +467,19 @@ def agc_calibration_copy(dst, src, nbytes, stream=None):
         raise AgcError(st, "agc_calibration_copy")
 
 
-def agc_debug_stream_rows(G, piece_bytes, out, wg_flush=False, blocks_per_wave=1, stream=None):
+def agc_debug_stream_rows(G, piece_bytes, out, wg_flush=False, blocks_per_wave=1, waves_per_simd=0, fma_per_row=0,
+                          stream=None):
     """The bare access pattern of the streaming passes over G (k x d view); piece_bytes = 0 reads only;
     wg_flush: pieces leave per workgroup after a barrier (the quantize pass's form) instead of per wave;
-    blocks_per_wave = 2 (reads only): the two-block walk of the max-abs scale pass."""
+    blocks_per_wave = 2 (reads only): the two-block walk of the max-abs scale pass; waves_per_simd = 4: built
+    for the quantize pass's occupancy; fma_per_row: dummy dependent multiply-adds per row and lane."""
     k, d = int(G.shape[0]), int(G.shape[1])
     need = max(16, k * (d // 256) * int(piece_bytes))
     if G.dim() != 2 or G.stride(1) != 1 or out.numel() * out.element_size() < need:
         raise AgcError(AGC_ESHAPE, f"agc_debug_stream_rows: out must hold {need} bytes")
     st = load().agc_debug_stream_rows(C.c_void_p(G.data_ptr()), G.stride(0), k, d, int(piece_bytes),
-                                      int(bool(wg_flush)), int(blocks_per_wave), C.c_void_p(out.data_ptr()),
-                                      _stream_handle(stream))
+                                      int(bool(wg_flush)), int(blocks_per_wave), int(waves_per_simd), int(fma_per_row),
+                                      C.c_void_p(out.data_ptr()), _stream_handle(stream))
     if st != AGC_OK:
         raise AgcError(st, "agc_debug_stream_rows")
 

@@ -666,15 +666,21 @@ agc_status agc_calibration_copy(void* dst_dev, const void* src_dev, int64_t byte
 }
 
 agc_status agc_debug_stream_rows(const float* G_dev, int64_t ldg, int k, int64_t d, int piece_bytes, int wg_flush,
-                                 int blocks_per_wave, void* out_dev, void* hip_stream)
+                                 int blocks_per_wave, int waves_per_simd, int fma_per_row, void* out_dev,
+                                 void* hip_stream)
 {
+    if (waves_per_simd != 0 && waves_per_simd != 4) return AGC_EINVAL;
+    if (fma_per_row != 0 && fma_per_row != 40 && fma_per_row != 100) return AGC_EINVAL;
+    if (fma_per_row != 0 && (waves_per_simd != 4 || !wg_flush || piece_bytes == 0 || blocks_per_wave != 1))
+        return AGC_EINVAL;
     if (!G_dev || !out_dev) return AGC_EINVAL;
     if (k < 1 || k > 65536 || d < 1 || d > ((int64_t)1 << 33)) return AGC_ESHAPE;
     if (piece_bytes < 0 || piece_bytes > 1024 || (piece_bytes & 15)) return AGC_EINVAL;
     if (blocks_per_wave != 1 && !(blocks_per_wave == 2 && piece_bytes == 0)) return AGC_EINVAL;
     if (ldg < d || (ldg & 3) || (reinterpret_cast<uintptr_t>(G_dev) & 15u) || (reinterpret_cast<uintptr_t>(out_dev) & 15u))
         return AGC_EALIGN;
-    hipError_t e = agc::launch_stream_rows(G_dev, ldg, k, d, piece_bytes, wg_flush != 0, blocks_per_wave, out_dev,
+    hipError_t e = agc::launch_stream_rows(G_dev, ldg, k, d, piece_bytes, wg_flush != 0, blocks_per_wave,
+                                           waves_per_simd, fma_per_row, out_dev,
                                            reinterpret_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? AGC_OK : AGC_EHIP;
 }

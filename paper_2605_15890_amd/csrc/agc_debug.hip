@@ -35,9 +35,13 @@ typedef __attribute__((address_space(1))) f32x4_t* global_f32x4_w;
 // the row.  2: nothing is written until the workgroup has walked all rows; then, after one barrier,
 // its four blocks' pieces of every row leave as 4 * pieces contiguous pieces (whole, aligned lines).
 // V: neighbouring blocks a wave walks at once (V loads per row, 1 KiB apart); reads-only form.
-template <int WRITE, int V>
-__global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restrict__ G, int64_t ldg, int k,
-                                                            int64_t nblocks, int pieces, f32x4_t* out)
+// OCC: 0, or the number of waves per SIMD the kernel is built for (the quantize pass runs with four).
+// FMA: dummy arithmetic between the rows, FMA dependent multiply-adds per row and lane, unrolled (a
+// loop of unknown length between the loads would make the compiler wait for all of them); the
+// quantize pass issues about ninety vector instructions per row and lane.
+template <int WRITE, int V, int OCC, int FMA>
+__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_waves_per_eu(OCC == 0 ? 1 : OCC, OCC == 0 ? 8 : OCC)))
+void k_stream_rows(const float* __restrict__ G, int64_t ldg, int k, int64_t nblocks, int pieces, f32x4_t* out)
 {
     static_assert(V == 1 || WRITE == 0, "several blocks per wave: reads only");
     constexpr int P = V == 1 ? 4 : 2;  // rows in flight, as in the passes
@@ -73,10 +77,18 @@ __global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restr
                     for (int v = 0; v < V; ++v)
                         ring[r][v] = load_row4<false, true>(row + (int64_t)(j + P) * ldg + v * kBlockCoords, lc);
                 }
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    acc = fmaxf(acc, fmaxf(fmaxf(cur[v].x, cur[v].y), fmaxf(cur[v].z, cur[v].w)));
                 last = cur[0];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+#pragma unroll
+                    for (int it = 0; it < FMA / 4; ++it) {  // each round feeds the next
+                        cur[v].x = fmaf(cur[v].x, 1.0001f, cur[v].y);
+                        cur[v].y = fmaf(cur[v].y, 0.9999f, cur[v].z);
+                        cur[v].z = fmaf(cur[v].z, 1.0002f, cur[v].w);
+                        cur[v].w = fmaf(cur[v].w, 0.9998f, cur[v].x);
+                    }
+                    acc = fmaxf(acc, fmaxf(fmaxf(cur[v].x, cur[v].y), fmaxf(cur[v].z, cur[v].w)));
+                }
                 if (WRITE == 1 && lane < pieces)
                     __builtin_nontemporal_store(f32x4_t{last.x, last.y, last.z, last.w},
                                                 (global_f32x4_w)(out + (int64_t)j * stream_pieces + block * pieces + lane));
@@ -98,24 +110,42 @@ __global__ __launch_bounds__(kWgThreads) void k_stream_rows(const float* __restr
     if (acc == 1.2345678e37f) out[0] = f32x4_t{acc, acc, acc, acc};  // keeps the loads alive; never true for finite data in practice
 }
 
+template <int WRITE, int V, int OCC, int FMA>
+static void launch_stream_rows_as(unsigned grid, hipStream_t stream, const float* G, int64_t ldg, int k,
+                                  int64_t nblocks, int pieces, f32x4_t* o)
+{
+    hipLaunchKernelGGL((k_stream_rows<WRITE, V, OCC, FMA>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
+                       pieces, o);
+}
+
 hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, int wg_flush,
-                              int blocks_per_wave, void* out, hipStream_t stream)
+                              int blocks_per_wave, int waves_per_simd, int fma_per_row, void* out, hipStream_t stream)
 {
     const int64_t nblocks = d / kBlockCoords;
     const int64_t units = nblocks / blocks_per_wave;  // whole runs of blocks_per_wave blocks
     if (units == 0) return hipSuccess;
     const unsigned grid = (unsigned)((units + kWavesPerWg - 1) / kWavesPerWg);
     f32x4_t* o = static_cast<f32x4_t*>(out);
-    if (blocks_per_wave == 2)
-        hipLaunchKernelGGL((k_stream_rows<0, 2>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks, 0, o);
-    else if (piece_bytes == 0)
-        hipLaunchKernelGGL((k_stream_rows<0, 1>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks, 0, o);
-    else if (!wg_flush)
-        hipLaunchKernelGGL((k_stream_rows<1, 1>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
-                           piece_bytes / 16, o);
-    else
-        hipLaunchKernelGGL((k_stream_rows<2, 1>), dim3(grid), dim3(kWgThreads), 0, stream, G, ldg, k, nblocks,
-                           piece_bytes / 16, o);
+    const int pieces = piece_bytes / 16;
+    const bool four = waves_per_simd == 4;
+    if (fma_per_row != 0) {  // arithmetic stand-in: the quantize pass's form only
+        if (!four || !wg_flush || piece_bytes == 0 || blocks_per_wave != 1) return hipErrorInvalidValue;
+        if (fma_per_row == 40) launch_stream_rows_as<2, 1, 4, 40>(grid, stream, G, ldg, k, nblocks, pieces, o);
+        else if (fma_per_row == 100) launch_stream_rows_as<2, 1, 4, 100>(grid, stream, G, ldg, k, nblocks, pieces, o);
+        else return hipErrorInvalidValue;
+    } else if (blocks_per_wave == 2) {
+        if (four) launch_stream_rows_as<0, 2, 4, 0>(grid, stream, G, ldg, k, nblocks, 0, o);
+        else launch_stream_rows_as<0, 2, 0, 0>(grid, stream, G, ldg, k, nblocks, 0, o);
+    } else if (piece_bytes == 0) {
+        if (four) launch_stream_rows_as<0, 1, 4, 0>(grid, stream, G, ldg, k, nblocks, 0, o);
+        else launch_stream_rows_as<0, 1, 0, 0>(grid, stream, G, ldg, k, nblocks, 0, o);
+    } else if (!wg_flush) {
+        if (four) launch_stream_rows_as<1, 1, 4, 0>(grid, stream, G, ldg, k, nblocks, pieces, o);
+        else launch_stream_rows_as<1, 1, 0, 0>(grid, stream, G, ldg, k, nblocks, pieces, o);
+    } else {
+        if (four) launch_stream_rows_as<2, 1, 4, 0>(grid, stream, G, ldg, k, nblocks, pieces, o);
+        else launch_stream_rows_as<2, 1, 0, 0>(grid, stream, G, ldg, k, nblocks, pieces, o);
+    }
     return hipGetLastError();
 }
 

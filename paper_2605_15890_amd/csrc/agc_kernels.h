@@ -201,6 +201,6 @@ hipError_t launch_gd_update(float* beta, const float* ghat, float lr, int64_t d,
 // the bare row-walk access pattern of the streaming passes (piece_bytes = 0: reads only)
 hipError_t launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 hipError_t launch_stream_rows(const float* G, int64_t ldg, int k, int64_t d, int piece_bytes, int wg_flush,
-                              int blocks_per_wave, void* out, hipStream_t stream);
+                              int blocks_per_wave, int waves_per_simd, int fma_per_row, void* out, hipStream_t stream);
 
 }  // namespace agc

@@ -30,9 +30,9 @@ def test_stream_rows_touches_exactly_its_output_region(k, d, piece):
     nblocks = d // 256
     region = max(4, k * nblocks * piece // 4)            # floats
     canary = 12345.0
-    for flush in (False, True):
+    for flush, occ, fma in ((False, 0, 0), (True, 0, 0), (True, 4, 0), (True, 4, 100), (True, 4, 40), (False, 4, 0)):
         out = torch.full((region + 1024,), canary, dtype=torch.float32, device="cuda")
-        api.agc_debug_stream_rows(G, piece, out, wg_flush=flush)
+        api.agc_debug_stream_rows(G, piece, out, wg_flush=flush, waves_per_simd=occ, fma_per_row=fma)
         torch.cuda.synchronize()
         o = out.cpu().numpy()
         assert np.all(o[k * nblocks * piece // 4:] == canary)          # nothing past the region
@@ -47,6 +47,9 @@ def test_stream_rows_touches_exactly_its_output_region(k, d, piece):
         api.agc_debug_stream_rows(G, 0, out, blocks_per_wave=per_wave)
         torch.cuda.synchronize()
         assert bool((out == canary).all())
+    for bad in (dict(waves_per_simd=3), dict(fma_per_row=8, waves_per_simd=4), dict(fma_per_row=100)):
+        with pytest.raises(api.AgcError):
+            api.agc_debug_stream_rows(G, 0, out, **bad)
     with pytest.raises(api.AgcError):     # the two-block walk is a reads-only form
         api.agc_debug_stream_rows(G, piece, torch.empty(region + 1024, dtype=torch.float32, device="cuda"),
                                   blocks_per_wave=2)
