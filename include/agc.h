@@ -114,8 +114,10 @@ agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col
 
 /* Layer-wise scales (Sec. II-B: the quantizer "at layer-wise or bucket-wise granularity"): the d
  * coordinates are cut into n_layers consecutive layers, layer l = [layer_end[l-1], layer_end[l])
- * with layer_end[-1] = 0, and every worker gets one max-abs scale per layer,
- * scale_il = max over the layer of |f_i[m]|.  Everything else is the per-vector arithmetic with
+ * with layer_end[-1] = 0, and every worker gets one scale per layer, of the context's kind:
+ * scale_il = max over the layer of |f_i[m]|, or the Euclidean norm of the layer with the AGC_SCALE_L2
+ * tree started anew at the layer's first coordinate (blocks, segments, groups and supergroups are
+ * counted from there).  Everything else is the per-vector arithmetic with
  * the layer's scale in place of the vector's: inv16_il = (float)(L_i * 2^16 / scale_il), decode
  * weight (float)(((double)w_i * scale_il) / L_i); draws and payload layout do not change.  With
  * layers set, scales_dev of the per-step calls holds n x n_layers floats, [worker][layer]
@@ -124,7 +126,7 @@ agc_status agc_set_code(agc_ctx *ctx, const int32_t *row_ptr, const int32_t *col
  *   layer_end  host, n_layers ends, strictly ascending, all but the last multiples of 256 (a
  *              256-coordinate block lies in one layer), the last equal to d
  * 1 <= n_layers <= AGC_MAX_LAYERS; n_layers == 0 returns to one scale per vector.  Needs a context
- * with AGC_SCALE_MAXABS and bucket == 0 (AGC_EINVAL otherwise).  Synchronous (waits for the device,
+ * with bucket == 0 (AGC_EINVAL otherwise).  Synchronous (waits for the device,
  * replaces small tables); not available in agc_decode_noalloc, which has no context. */
 agc_status agc_set_layers(agc_ctx *ctx, int n_layers, const int64_t *layer_end);
 

@@ -450,23 +450,26 @@ def layer_ranges(ends, d):
     return list(zip([0] + ends[:-1], ends))
 
 
-def scales_layers(G, csr, ends):
-    """(n, n_layers) float32: largest magnitude of f_i inside every layer."""
+def scales_layers(G, csr, ends, scale_mode=1):
+    """(n, n_layers) float32: the scale of f_i inside every layer - its largest magnitude
+    (scale_mode 1), or its Euclidean norm with the summation tree started at the layer's first
+    coordinate (scale_mode 0): the layer taken as a vector of its own."""
     G, _ = _f32(G)
     ranges = layer_ranges(ends, G.shape[1])
+    one = scale_maxabs if int(scale_mode) == 1 else scale_l2
     out = np.zeros((csr.n, len(ranges)), dtype=np.float32)
     for i in range(csr.n):
         for l, (m0, m1) in enumerate(ranges):
-            out[i, l] = scale_maxabs(encode(G, csr, i, m0, m1))
+            out[i, l] = one(encode(G, csr, i, m0, m1))
     return out
 
 
-def encode_quantize_layers(G, csr, bits, seed, step_, ends, scales_in=None):
+def encode_quantize_layers(G, csr, bits, seed, step_, ends, scales_in=None, scale_mode=1):
     """Streams and (n, n_layers) scales: layer l of worker i is quantized with scale [i, l]."""
     G, _ = _f32(G)
     d = G.shape[1]
     ranges = layer_ranges(ends, d)
-    sc = scales_layers(G, csr, ends) if scales_in is None else np.asarray(scales_in, dtype=np.float32)
+    sc = scales_layers(G, csr, ends, scale_mode) if scales_in is None else np.asarray(scales_in, dtype=np.float32)
     streams = []
     for i in range(csr.n):
         codes = np.concatenate([codes_range(G, csr, i, int(bits[i]), sc[i, l], seed, step_, m0, m1)
@@ -482,8 +485,8 @@ def decode_layers(streams, scales, bits, w, mask, d, ends):
                            for l, (m0, m1) in enumerate(layer_ranges(ends, d))])
 
 
-def step_layers(G, csr, bits, w, mask, seed, step_, ends):
-    """One whole pass with layer-wise max-abs scales.  Returns (streams, scales (n, n_layers), ghat)."""
+def step_layers(G, csr, bits, w, mask, seed, step_, ends, scale_mode=1):
+    """One whole pass with layer-wise scales.  Returns (streams, scales (n, n_layers), ghat)."""
     G, _ = _f32(G)
-    streams, sc = encode_quantize_layers(G, csr, bits, seed, step_, ends)
+    streams, sc = encode_quantize_layers(G, csr, bits, seed, step_, ends, scale_mode=scale_mode)
     return streams, sc, decode_layers(streams, sc, bits, w, mask, G.shape[1], ends)

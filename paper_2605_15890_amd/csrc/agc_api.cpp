@@ -75,6 +75,13 @@ hipError_t dev_alloc(T** p, size_t count)
 void free_layers(agc_ctx* c)
 {
     if (c->ws.block_layer) (void)hipFree(const_cast<uint8_t*>(c->ws.block_layer));
+    if (c->ws.seg_first) (void)hipFree(const_cast<int*>(c->ws.seg_first));
+    if (c->ws.seg_blocks) (void)hipFree(const_cast<uint8_t*>(c->ws.seg_blocks));
+    if (c->ws.layer_seg) (void)hipFree(const_cast<int*>(c->ws.layer_seg));
+    c->ws.seg_first = nullptr;
+    c->ws.seg_blocks = nullptr;
+    c->ws.layer_seg = nullptr;
+    c->ws.nseg_layers = 0;
     if (c->ws.coef_layer) (void)hipFree(c->ws.coef_layer);
     if (c->ws.coef2_layer) (void)hipFree(c->ws.coef2_layer);
     c->ws.block_layer = nullptr;
@@ -351,8 +358,7 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
         free_layers(c);
         return AGC_OK;
     }
-    if (c->opts.bucket || c->opts.scale_mode != AGC_SCALE_MAXABS)
-        return fail(c, AGC_EINVAL, "layer-wise scales need AGC_SCALE_MAXABS and bucket == 0");
+    if (c->opts.bucket) return fail(c, AGC_EINVAL, "layer-wise scales need bucket == 0");
     if (!layer_end) return fail(c, AGC_EINVAL, "layer_end is null");
     int64_t prev = 0;
     for (int l = 0; l < n_layers; ++l) {
@@ -372,6 +378,27 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
             layer_of[(size_t)blk] = (uint8_t)l;
         }
     }
+    // Euclidean scale: the segments of every layer's own summation tree
+    const bool l2 = c->opts.scale_mode == AGC_SCALE_L2;
+    std::vector<int> seg_first, layer_seg;
+    std::vector<uint8_t> seg_blocks;
+    if (l2) {
+        int64_t first = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int64_t end_block = (layer_end[l] + 255) / 256;  // one past the layer's last block
+            layer_seg.push_back((int)seg_first.size());
+            for (int64_t blk = first; blk < end_block; blk += 4) {
+                seg_first.push_back((int)blk);
+                seg_blocks.push_back((uint8_t)std::min<int64_t>(4, end_block - blk));
+            }
+            first = end_block;
+        }
+        layer_seg.push_back((int)seg_first.size());
+    }
+    int* d_seg_first = nullptr;
+    uint8_t* d_seg_blocks = nullptr;
+    int* d_layer_seg = nullptr;
+    double* d_part_sq = nullptr;
     uint8_t* d_layer = nullptr;
     agc::WorkerQ* d_wq = nullptr;
     float *d_c1 = nullptr, *d_c2 = nullptr;
@@ -379,10 +406,19 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
     const size_t entries = (size_t)c->n * (size_t)n_layers;
     const int rows = std::max(agc::kMaxSlots, n_layers * agc::kLayerSub);
     e = dev_alloc(&d_layer, (size_t)nblocks);
-    if (e == hipSuccess && rows > c->ws.max_rows) {  // several rows of running maxima per layer
+    if (e == hipSuccess && !l2 && rows > c->ws.max_rows) {  // several rows of running maxima per layer
         e = dev_alloc(&d_max, (size_t)rows * c->n);
         if (e == hipSuccess) e = hipMemset(d_max, 0, sizeof(uint32_t) * (size_t)rows * c->n);
         if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
+    if (e == hipSuccess && l2) {
+        e = dev_alloc(&d_seg_first, seg_first.size());
+        if (e == hipSuccess) e = dev_alloc(&d_seg_blocks, seg_blocks.size());
+        if (e == hipSuccess) e = dev_alloc(&d_layer_seg, layer_seg.size());
+        if (e == hipSuccess) e = dev_alloc(&d_part_sq, seg_first.size() * (size_t)c->n);
+        if (e == hipSuccess) e = hipMemcpy(d_seg_first, seg_first.data(), sizeof(int) * seg_first.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(d_seg_blocks, seg_blocks.data(), seg_blocks.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(d_layer_seg, layer_seg.data(), sizeof(int) * layer_seg.size(), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) e = dev_alloc(&d_wq, entries);
     if (e == hipSuccess) e = dev_alloc(&d_c1, entries);
@@ -390,6 +426,10 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
     if (e == hipSuccess) e = hipMemcpy(d_layer, layer_of.data(), (size_t)nblocks, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         if (d_layer) (void)hipFree(d_layer);
+        if (d_seg_first) (void)hipFree(d_seg_first);
+        if (d_seg_blocks) (void)hipFree(d_seg_blocks);
+        if (d_layer_seg) (void)hipFree(d_layer_seg);
+        if (d_part_sq) (void)hipFree(d_part_sq);
         if (d_max) (void)hipFree(d_max);
         if (d_wq) (void)hipFree(d_wq);
         if (d_c1) (void)hipFree(d_c1);
@@ -406,6 +446,14 @@ agc_status agc_set_layers(agc_ctx* c, int n_layers, const int64_t* layer_end)
         c->ws.max_rows = rows;
     }
     c->ws.block_layer = d_layer;
+    if (l2) {  // at least as many segments as the per-vector tree has: the array serves both
+        (void)hipFree(c->ws.part_sq);
+        c->ws.part_sq = d_part_sq;
+        c->ws.seg_first = d_seg_first;
+        c->ws.seg_blocks = d_seg_blocks;
+        c->ws.layer_seg = d_layer_seg;
+        c->ws.nseg_layers = (int64_t)seg_first.size();
+    }
     c->ws.coef_layer = d_c1;
     c->ws.coef2_layer = d_c2;
     c->ws.n_layers = n_layers;

@@ -111,6 +111,12 @@ struct Workspace {
     // wq then holds one table per layer, [layer][n].
     const uint8_t* block_layer;  // [ceil(d/256)]
     int n_layers;
+    // Euclidean scale per layer: the summation tree starts anew in every layer, so the segments
+    // (up to four blocks) are counted from each layer's first block
+    const int* seg_first;        // [nseg_layers] first block of the segment
+    const uint8_t* seg_blocks;   // [nseg_layers] its number of blocks, 1..4
+    const int* layer_seg;        // [n_layers + 1] first segment of every layer
+    int64_t nseg_layers;
     float* coef_layer;    // [n_layers][n]
     float* coef2_layer;   // [n_layers][n]
 };

@@ -39,6 +39,8 @@ struct ScaleArgs {
     double* part_sq;
     const WindowRec* win;  // monotone-interval codes only
     const uint8_t* block_layer;  // layer-wise scales only (max-abs): the layer of every block
+    const int* seg_first;        // layer-wise Euclidean scales only: the segments of the layers
+    const uint8_t* seg_blocks;
 };
 
 // the same 32-bit word seen as device memory (store without address-space checks)
@@ -212,11 +214,19 @@ __global__ __launch_bounds__(kWave * WAVES) void k_scale_pass(const float* __res
         }
         return;
     }
-    if (base < a.d) {
-        const LaneCoords lc = lane_coords(base, lane, a.d);
+    // Euclidean scale per layer: segment `seg` is the table's run of up to four blocks (the tree of
+    // a layer starts at the layer's first block); a wave past the run contributes nothing
+    int64_t sq_base = base;
+    bool sq_has = base < a.d;
+    if (a.seg_first) {
+        sq_base = ((int64_t)a.seg_first[seg] + wave) * (int64_t)kBlockCoords;
+        sq_has = wave < (int)a.seg_blocks[seg];
+    }
+    if (sq_has) {
+        const LaneCoords lc = lane_coords(sq_base, lane, a.d);
         EpiSumSq epi{accd, lane};
-        encode_block<S>(G + base, a.ldg, a.n, a.k, B, lc, epi);
-    } else {  // a block past the end of the vector contributes nothing
+        encode_block<S>(G + sq_base, a.ldg, a.n, a.k, B, lc, epi);
+    } else {  // a block past the end of the vector (or of the layer's last segment) contributes nothing
         for (int i = lane; i < a.n; i += kWave) accd[i] = 0.0;
     }
     __syncthreads();
@@ -282,8 +292,10 @@ hipError_t launch_scale_pass(const float* G, int64_t ldg, int n, int k, int64_t 
                              const CodeDev& code, int scale_mode, const Workspace& ws,
                              hipStream_t stream)
 {
-    ScaleArgs a{ldg, n, k, d, ws.nseg, ws.part_max, ws.part_sq, code.win, ws.n_layers > 0 ? ws.block_layer : nullptr};
-    if (a.block_layer && scale_mode != 1) return hipErrorInvalidValue;  // layer-wise scales are max-abs scales
+    const bool layers = ws.n_layers > 0;
+    ScaleArgs a{ldg, n, k, d, layers && scale_mode == 0 ? ws.nseg_layers : ws.nseg, ws.part_max, ws.part_sq, code.win,
+                layers && scale_mode == 1 ? ws.block_layer : nullptr,
+                layers && scale_mode == 0 ? ws.seg_first : nullptr, layers && scale_mode == 0 ? ws.seg_blocks : nullptr};
     if (code.band < 0 && !code.win) return hipErrorInvalidValue;  // the window driver reads the records
     switch (code.band) {
         case 1: return launch_scale_pass_s<1>(G, code, a, scale_mode, stream);
@@ -395,18 +407,48 @@ __global__ __launch_bounds__(kWgThreads) void k_scale_finalize(int n, QuantStrea
 // the layer's maxima; every (worker, layer) gets its scale, and table l of the quantize pass gets the
 // worker's record with the multiplier and the decode weight of that layer (the formulas of the
 // per-vector case with the layer's scale).  The rows are handed back zeroed.
+// Euclidean scale (MODE 0): thread i walks the layer's segment sums [segment][worker] in the order of
+// the tree - 64 segments into a group, 64 groups into a supergroup, supergroups into the total,
+// every sum from 0.0 in index order - with the loads of eight segments requested together.
+template <int MODE>
 __global__ __launch_bounds__(kWgThreads) void k_scale_finalize_layers(int n, QuantStreams out, StepWeights sw,
                                                                       Workspace ws, float* scales)
 {
     const int l = blockIdx.x;
     for (int i = threadIdx.x; i < n; i += kWgThreads) {
-        uint32_t m = 0u;
-        for (int r = 0; r < kLayerSub; ++r) {
-            uint32_t* p = ws.part_max + ((int64_t)l * kLayerSub + r) * n + i;
-            m = max(m, __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float scale;
+        if (MODE == 1) {
+            uint32_t m = 0u;
+            for (int r = 0; r < kLayerSub; ++r) {
+                uint32_t* p = ws.part_max + ((int64_t)l * kLayerSub + r) * n + i;
+                m = max(m, __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                __hip_atomic_store(p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            scale = __uint_as_float(m);
+        } else {
+            const int64_t s_begin = ws.layer_seg[l], s_end = ws.layer_seg[l + 1];
+            const double* part = ws.part_sq + i;
+            double total = 0.0;
+            for (int64_t u0 = s_begin; u0 < s_end; u0 += (int64_t)kGroupSegs * kGroupSegs) {  // supergroups
+                const int64_t u1 = u0 + (int64_t)kGroupSegs * kGroupSegs < s_end ? u0 + (int64_t)kGroupSegs * kGroupSegs : s_end;
+                double super = 0.0;
+                for (int64_t g0 = u0; g0 < u1; g0 += kGroupSegs) {  // groups
+                    const int64_t g1 = g0 + kGroupSegs < u1 ? g0 + kGroupSegs : u1;
+                    double group = 0.0;
+                    for (int64_t s0 = g0; s0 < g1; s0 += 8) {
+                        double v[8];
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) v[t] = s0 + t < g1 ? part[(s0 + t) * n] : 0.0;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            if (s0 + t < g1) group = group + v[t];
+                    }
+                    super = super + group;
+                }
+                total = total + super;
+            }
+            scale = (float)sqrt(total);
         }
-        const float scale = __uint_as_float(m);
         scales[(int64_t)i * ws.n_layers + l] = scale;
         const int b = out.bits[i];
         const uint32_t flush = (i == n - 1 || out.stage_start[i + 1] == 0) ? 1u : 0u;
@@ -424,9 +466,12 @@ hipError_t launch_scale_finalize(int n, int scale_mode, const QuantStreams& out,
                                  const Workspace& ws, float* scales, hipStream_t stream)
 {
     if (ws.n_layers > 0) {
-        if (scale_mode != 1) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(k_scale_finalize_layers, dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, out, sw, ws,
-                           scales);
+        if (scale_mode == 1)
+            hipLaunchKernelGGL((k_scale_finalize_layers<1>), dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, out, sw,
+                               ws, scales);
+        else
+            hipLaunchKernelGGL((k_scale_finalize_layers<0>), dim3(ws.n_layers), dim3(kWgThreads), 0, stream, n, out, sw,
+                               ws, scales);
         return hipGetLastError();
     }
     if (scale_mode == 0) {

@@ -1,4 +1,4 @@
-"""GPU parity of layer-wise max-abs scales (agc_set_layers; Sec. II-B: the quantizer "at layer-wise
+"""GPU parity of layer-wise scales (agc_set_layers; Sec. II-B: the quantizer "at layer-wise
 or bucket-wise granularity") through the C ABI against the oracle's layer-wise composition: streams
 bit for bit, scales as bit patterns, the estimate identical, for every encode driver, the fused and
 the two-pass step, the stand-alone and the two-track decode; and the error paths."""
@@ -14,11 +14,12 @@ from gpu_util import cyclic_csr, monotone_csr, random_csr, to_device
 pytestmark = pytest.mark.gpu
 
 
-def _run(G_host, n, k, code, bits, w, mask, seed, step, ends, unfused, path=None, allow_1bit=False):
+def _run(G_host, n, k, code, bits, w, mask, seed, step, ends, unfused, path=None, allow_1bit=False,
+         scale_mode=api.AGC_SCALE_MAXABS):
     import torch
     d = G_host.shape[1]
     G = to_device(G_host)
-    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS, unfused_step=unfused, allow_1bit=allow_1bit)
+    ctx = api.Context(n, k, d, scale_mode=scale_mode, unfused_step=unfused, allow_1bit=allow_1bit)
     try:
         ctx.agc_set_code(*code)
         if path is not None:
@@ -38,10 +39,10 @@ def _run(G_host, n, k, code, bits, w, mask, seed, step, ends, unfused, path=None
         ctx.close()
 
 
-def _check(G_host, k, code, bits, w, mask, seed, step, ends, out, tag):
+def _check(G_host, k, code, bits, w, mask, seed, step, ends, out, tag, scale_mode=api.AGC_SCALE_MAXABS):
     streams, scales, ghat = out
     csr = O.Csr(code[0], code[1], code[2], k)
-    o_streams, o_scales, o_ghat = O.step_layers(G_host, csr, bits, w, mask, seed, step, ends)
+    o_streams, o_scales, o_ghat = O.step_layers(G_host, csr, bits, w, mask, seed, step, ends, scale_mode=scale_mode)
     assert np.array_equal(scales.view(np.uint32), o_scales.view(np.uint32)), tag
     for i in range(csr.n):
         assert np.array_equal(streams[i], o_streams[i]), (tag, "stream", i)
@@ -84,6 +85,71 @@ def test_layerwise_step_matches_oracle(kind, d, ends, unfused):
     mask[1] = 1
     out = _run(G_host, n, k, code, bits, w, mask, 41, 6, ends, unfused, path)
     _check(G_host, k, code, bits, w, mask, 41, 6, ends, out, f"{kind} d={d} unfused={unfused}")
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("kind,d,ends", [
+    ("cyclic3", 5000, [256, 512, 4864, 5000]),           # one-block layers, a ragged last layer
+    ("cyclic4", 256 * 700 + 9, [256 * 3, 256 * 300, 256 * 301, 256 * 700 + 9]),   # layers of 3, 297, 1 and 400 blocks: partial last segments, a group boundary inside
+    ("window4", 70001, [256 * 7, 256 * 100, 256 * 101, 70001]),
+    ("generic", 3000, [768, 3000]),
+])
+def test_layerwise_euclidean_step_matches_oracle(kind, d, ends, unfused):
+    """The Euclidean scale per layer: every layer has a summation tree of its own, started at the
+    layer's first block."""
+    rng = np.random.default_rng(len(kind) * 2000 + d)
+    if kind.startswith("cyclic"):
+        s = int(kind[6:])
+        n = k = 6
+        code = cyclic_csr(rng, n, s)
+        path = s
+    elif kind.startswith("window"):
+        n, k = 9, 6
+        code = monotone_csr(rng, n, k, 4)
+        path = None
+    else:
+        n, k = 5, 4
+        code = random_csr(rng, n, k)
+        path = 0
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    lo = 0
+    for l, hi in enumerate(ends):
+        G_host[:, lo:hi] *= np.float32(10.0 ** (l % 3 - 1))
+        lo = hi
+    bits = rng.integers(2, 9, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = (rng.uniform(size=n) < 0.7).astype(np.uint8)
+    mask[0] = 1
+    out = _run(G_host, n, k, code, bits, w, mask, 17, 4, ends, unfused, path, scale_mode=api.AGC_SCALE_L2)
+    _check(G_host, k, code, bits, w, mask, 17, 4, ends, out, f"l2 {kind} d={d}", scale_mode=api.AGC_SCALE_L2)
+
+
+def test_one_euclidean_layer_equals_the_per_vector_step():
+    import torch
+    rng = np.random.default_rng(91)
+    n = k = 5
+    d = 256 * 4 * 64 * 3 + 1000          # more than two groups of segments
+    code = cyclic_csr(rng, n, 2)
+    G_host = rng.standard_normal((k, d)).astype(np.float32)
+    bits = rng.integers(2, 6, n).astype(np.uint8)
+    w = rng.uniform(0.5, 1.5, n).astype(np.float32)
+    mask = np.ones(n, dtype=np.uint8)
+    G = to_device(G_host)
+    ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_L2)
+    try:
+        ctx.agc_set_code(*code)
+        res = []
+        for ends in ([], [d]):
+            ctx.agc_set_layers(ends)
+            codes, scales, ghat = ctx.alloc_outputs(bits)
+            ctx.agc_step(G, bits, w, mask, 3, 9, codes, scales, ghat)
+            torch.cuda.synchronize()
+            res.append(([c.cpu().numpy() for c in codes], scales.cpu().numpy().reshape(n, -1), ghat.cpu().numpy()))
+        assert np.array_equal(res[0][1][:, 0].view(np.uint32), res[1][1][:, 0].view(np.uint32))
+        assert all(np.array_equal(a, b) for a, b in zip(res[0][0], res[1][0]))
+        assert np.array_equal(res[0][2].view(np.uint32), res[1][2].view(np.uint32))
+    finally:
+        ctx.close()
 
 
 def test_one_layer_equals_the_per_vector_step_and_layers_can_be_switched_off():
@@ -192,7 +258,7 @@ def test_set_layers_argument_errors():
         assert ctx.agc_scales_per_worker() == 2
     finally:
         ctx.close()
-    for kw in (dict(scale_mode=api.AGC_SCALE_L2), dict(scale_mode=api.AGC_SCALE_MAXABS, bucket=256)):
+    for kw in (dict(scale_mode=api.AGC_SCALE_L2, bucket=256), dict(scale_mode=api.AGC_SCALE_MAXABS, bucket=256)):
         ctx = api.Context(4, 4, d, **kw)
         try:
             with pytest.raises(api.AgcError) as e:

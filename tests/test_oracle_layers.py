@@ -36,6 +36,47 @@ def test_one_layer_is_the_per_vector_step():
     assert np.array_equal(g1.view(np.uint32), g2.view(np.uint32))
 
 
+def test_one_layer_is_the_per_vector_step_also_with_the_euclidean_scale():
+    rng = np.random.default_rng(11)
+    n = k = 4
+    d = 2500
+    row_ptr, col, val = _cyclic(rng, n, 2)
+    csr = O.Csr(row_ptr, col, val, k)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    bits = np.array([2, 4, 6, 9], dtype=np.uint8)
+    w = rng.uniform(0.5, 2.0, n).astype(np.float32)
+    mask = np.ones(n, dtype=np.uint8)
+    s1, c1, g1 = O.step(G, csr, bits, w, mask, 1, 2, O.SCALE_L2)
+    s2, c2, g2 = O.step_layers(G, csr, bits, w, mask, 1, 2, [d], scale_mode=O.SCALE_L2)
+    assert np.array_equal(c1.view(np.uint32), c2[:, 0].view(np.uint32))
+    assert all(np.array_equal(a, b) for a, b in zip(s1, s2))
+    assert np.array_equal(g1.view(np.uint32), g2.view(np.uint32))
+
+
+def test_layer_norms_are_the_norms_of_the_slices():
+    """Every layer's Euclidean scale against an exactly rounded sum of the slice's squares
+    (math.fsum over the binary64 squares, which are exact), to the last few units of binary32."""
+    import math
+    rng = np.random.default_rng(12)
+    n = k = 3
+    d = 5000
+    row_ptr, col, val = _cyclic(rng, n, 2)
+    csr = O.Csr(row_ptr, col, val, k)
+    G = rng.standard_normal((k, d)).astype(np.float32)
+    ends = [256, 1280, 4864, 5000]
+    sc = O.scales_layers(G, csr, ends, scale_mode=O.SCALE_L2)
+    for i in range(n):
+        f = O.encode(G, csr, i).astype(np.float64)
+        for l, (m0, m1) in enumerate(O.layer_ranges(ends, d)):
+            exact = math.sqrt(math.fsum(float(x) * float(x) for x in f[m0:m1]))
+            assert abs(float(sc[i, l]) - exact) <= 2e-7 * exact, (i, l)
+    # and a layer that starts off the origin uses a tree of its own: equal slices, equal norms
+    G2 = np.concatenate([G[:, 1280:4864], G[:, 1280:4864]], axis=1)
+    sc2 = O.scales_layers(G2, csr, [3584, 7168], scale_mode=O.SCALE_L2)
+    assert np.array_equal(sc2[:, 0].view(np.uint32), sc2[:, 1].view(np.uint32))
+    assert np.array_equal(sc2[:, 0].view(np.uint32), sc[:, 2].view(np.uint32))
+
+
 def test_layer_scales_are_the_exact_maxima_of_integer_data():
     """Integer code and integer gradients: every f_i[m] is an exact integer, so the scales must
     equal the maxima numpy finds in the integer product, layer by layer."""
