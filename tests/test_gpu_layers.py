@@ -268,7 +268,8 @@ def test_set_layers_argument_errors():
             ctx.close()
 
 
-def test_layerwise_scales_at_full_size_on_the_layered_workload():
+@pytest.mark.parametrize("scale_mode", [api.AGC_SCALE_MAXABS, api.AGC_SCALE_L2])
+def test_layerwise_scales_at_full_size_on_the_layered_workload(scale_mode):
     """The resnet18-sized workload (d = 11.7 M, partial gradients whose magnitude changes by up to
     10^3 from one of its 60 layers to the next) with one scale per layer and worker: every scale
     against the oracle over the whole vector; codes and the estimate in windows placed around layer
@@ -287,7 +288,7 @@ def test_layerwise_scales_at_full_size_on_the_layered_workload():
     mask = I.arrival_mask(cfg, p, step)
     outs = []
     for unfused in (False, True):
-        ctx = api.Context(n, k, d, scale_mode=api.AGC_SCALE_MAXABS, allow_1bit=cfg.allow_1bit, unfused_step=unfused)
+        ctx = api.Context(n, k, d, scale_mode=scale_mode, allow_1bit=cfg.allow_1bit, unfused_step=unfused)
         ctx.agc_set_code(row_ptr, col, val)
         assert ctx.agc_code_path() == cfg.s
         ctx.agc_set_layers(ends)
@@ -308,7 +309,7 @@ def test_layerwise_scales_at_full_size_on_the_layered_workload():
     torch.cuda.empty_cache()
     csr = O.Csr(row_ptr, col, val, k)
     print("[layers] oracle scales", flush=True)
-    o_scales = O.scales_layers(G_host, csr, ends)
+    o_scales = O.scales_layers(G_host, csr, ends, scale_mode=scale_mode)
     assert np.array_equal(scales_h.view(np.uint32), o_scales.view(np.uint32))
     # the layers really differ: per worker the largest and the smallest layer scale are far apart
     assert np.all(o_scales.max(axis=1) > 50 * o_scales.min(axis=1))
