@@ -268,10 +268,12 @@ struct RingShapeT {
     static constexpr int R = S + P;
     static constexpr int NSTASH = S > 1 ? S - 1 : 1;
 };
-// The prefetch distance is a property of the epilogue (Epi::kPrefetchRows): the scale pass has
-// registers to spare and keeps many rows in flight, the quantize pass does not.
+// The prefetch distance is a property of the epilogue (Epi::kPrefetchRows).  Quantize pass: two
+// rows ahead (measured 2/3/4/6/8/10 rows: 1.393/1.402/1.400/1.411/1.419/1.414 ms on the metric
+// workload, two rows also best on the smaller ones: deeper prefetch only costs registers, the
+// pass does not wait for its loads).  One-block scale pass: four.
 #ifndef AGC_PREFETCH_ROWS
-#define AGC_PREFETCH_ROWS 4
+#define AGC_PREFETCH_ROWS 2
 #endif
 #ifndef AGC_SCALE_PREFETCH_ROWS
 #define AGC_SCALE_PREFETCH_ROWS 4
