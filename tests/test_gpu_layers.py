@@ -57,6 +57,7 @@ def _check(G_host, k, code, bits, w, mask, seed, step, ends, out, tag, scale_mod
     ("window4", 70001, [256 * 7, 256 * 100, 256 * 101, 70001]),
     ("generic", 3000, [768, 3000]),
     ("cyclic1", 300, [256, 300]),
+    ("cyclic2", 100, [100]),                             # less than one block, one layer
 ])
 def test_layerwise_step_matches_oracle(kind, d, ends, unfused):
     rng = np.random.default_rng(len(kind) * 1000 + d)
@@ -93,6 +94,7 @@ def test_layerwise_step_matches_oracle(kind, d, ends, unfused):
     ("cyclic4", 256 * 700 + 9, [256 * 3, 256 * 300, 256 * 301, 256 * 700 + 9]),   # layers of 3, 297, 1 and 400 blocks: partial last segments, a group boundary inside
     ("window4", 70001, [256 * 7, 256 * 100, 256 * 101, 70001]),
     ("generic", 3000, [768, 3000]),
+    ("cyclic2", 100, [100]),
 ])
 def test_layerwise_euclidean_step_matches_oracle(kind, d, ends, unfused):
     """The Euclidean scale per layer: every layer has a summation tree of its own, started at the
