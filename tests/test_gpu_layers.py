@@ -27,14 +27,14 @@ def _run(G_host, n, k, code, bits, w, mask, seed, step, ends, unfused, path=None
         ctx.agc_set_layers(ends)
         assert ctx.agc_scales_per_worker() == len(ends)
         codes, scales, ghat = ctx.alloc_outputs(bits)
-        assert tuple(scales.shape) == (n, len(ends))
+        assert scales.numel() == n * len(ends)
         for c in codes:
             c.fill_(0xA5)
         scales.fill_(-7.0)
         ghat.fill_(float("nan"))
         ctx.agc_step(G, bits, w, mask, seed, step, codes, scales, ghat)
         torch.cuda.synchronize()
-        return [c.cpu().numpy() for c in codes], scales.cpu().numpy(), ghat.cpu().numpy()
+        return [c.cpu().numpy() for c in codes], scales.cpu().numpy().reshape(n, len(ends)), ghat.cpu().numpy()
     finally:
         ctx.close()
 
