@@ -311,7 +311,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--scale", default="maxabs", choices=["maxabs", "l2"])
     ap.add_argument("--code", default="cyclic", choices=["cyclic", "interval"])
